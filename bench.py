@@ -1,0 +1,135 @@
+"""Benchmark of the hot path on one MI355X.
+
+A step = one classical RK4 step (4 x [ghost fill -> stencils -> right-hand side -> stage update])
+of the 24-field system on the ~1e5-block adaptive tree ("C5"), inputs resident in HBM.
+Prints ONE JSON line: block-point right-hand-side updates per second (fp64, per variable), the
+HBM roofline of the dominant kernel measured live with events on the launch stream, and the CPU
+oracle timed on this machine's host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# Algorithmic HBM bytes per block-point and variable of one RK stage launch (fused kernel, zipped in,
+# zipped out; ghost reads are re-reads of neighbours' owned data and count as cache traffic):
+#   first  stage: read u, write acc, write stage                   = 24 B
+#   middle stages: read stage, read u, read+write acc, write stage = 40 B   (twice)
+#   last   stage: read stage, read acc, read+write u               = 32 B
+STAGE_BYTES = (24.0, 40.0, 40.0, 32.0)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="C5", help="workload name from synthdata.CONFIGS (default: the headline one)")
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-blocks", type=int, default=12000)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_2007_12792_amd as octfd
+    import synthdata as sd
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the hot path has no CPU fallback")
+    dev = torch.device("cuda:0")
+    cfg = sd.CONFIGS[args.config]
+    kind = octfd.KINDS[cfg["kind"]]
+    if octfd.nvar_in(kind) != octfd.nvar_out(kind):
+        sys.exit("bench.py: the timed step is rk_step; choose a workload whose kind can be stepped")
+    p = sd.tree_params(args.config, args.seed)
+    t0 = time.time()
+    tree = octfd.Tree.build(**p)
+    t_build = time.time() - t0
+    leaves = tree.leaves
+    nb, V = tree.n, octfd.nvar_in(kind)
+    u = sd.make_fields(args.config, leaves, args.seed, device=dev)
+    u0 = u.clone()
+    ws = torch.empty(tree.rk_workspace_bytes(kind) // 8, dtype=torch.float64, device=dev)
+    dt, sg = sd.time_step(cfg["lmax"]), sd.KO_SIGMA
+    tree.upload()
+
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        u.copy_(u0)
+        tree.rk_step(kind, u, dt, ws, sigma=sg, stream=stream)
+    u.copy_(u0)
+    # the launches go to `stream`; the events are recorded on the same stream
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    ev[0].record(stream)
+    for i in range(args.steps):
+        tree.rk_step(kind, u, dt, ws, sigma=sg, stream=stream)
+        ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - w0
+    per_step_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
+    total_ms = ev[0].elapsed_time(ev[-1])
+    ms_per_step = total_ms / args.steps
+    updates_per_step = nb * 512 * V * 4
+    value = updates_per_step / (ms_per_step * 1e-3)
+
+    # dominant kernel = the fused right-hand-side/stage kernel, launched 4 times per step and nothing else
+    # runs in the timed region: average launch duration = region / (4 * steps)
+    launch_ms = total_ms / (4 * args.steps)
+    bytes_per_launch = sum(STAGE_BYTES) / 4.0 * nb * 512 * V
+    achieved = bytes_per_launch / (launch_ms * 1e-3) / 1e9
+    out = {
+        "metric": "block-point RHS updates/sec (fp64, per var) + achieved HBM GB/s, 1 GPU",
+        "value": value, "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "%s: %s RK4 step, 2:1-balanced octree levels %d-%d, %d blocks of 8^3 (pad 3), %d fields, KO sigma %.1f, seed %d"
+                   % (args.config, cfg["kind"], cfg["lmin"], cfg["lmax"], nb, V, sg, args.seed),
+                   "n_blocks": nb, "n_vars": V, "rhs_evals_per_step": 4,
+                   "zipped_state_GB": nb * 512 * V * 8 / 1e9, "tree_build_s": t_build,
+                   "ms_per_step_all": per_step_ms, "wall_s_timed_region": wall},
+        "roofline": {"bound": "hbm", "kernel": "k_rhs<%s, zipped in, RK-stage epilogue> (4 launches per step)" % cfg["kind"],
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "launch_ms": launch_ms, "algorithmic_bytes_per_launch": bytes_per_launch, "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        to = oracle.Tree.build(**p)
+        assert (to.leaves == leaves).all()
+        ns = min(args.cpu_sample_blocks, nb)
+        start = (nb - ns) // 2
+        blocks = np.arange(start, start + ns)
+        uh = u0.cpu().numpy()
+        threads = len(os.sched_getaffinity(0))
+        omp = os.environ.get("OMP_NUM_THREADS")
+        if omp:
+            threads = min(threads, int(omp))
+        c0 = time.perf_counter()
+        ref = to.F(kind, uh, sigma=sg, blocks=blocks)
+        cpu_s = time.perf_counter() - c0
+        # also use the sample as a live parity check of the kernel that was just timed
+        k1 = torch.empty((V, nb, 8, 8, 8), dtype=torch.float64, device=dev)
+        tree.rhs_eval_zipped(kind, u0, k1, sigma=sg)
+        got = k1[:, start:start + ns].cpu().numpy()
+        ok = bool((np.abs(got - ref) <= 1e-12 * np.abs(ref) + 1e-13).all())
+        out["cpu_baseline"] = {"value": ns * 512 * V / cpu_s, "unit": "updates/s", "cores": threads, "kind": "oracle",
+                               "sample": "one right-hand-side evaluation (unzip->rhs->zip) of %d contiguous Morton-order blocks "
+                                         "(%d..%d) of the same tree and fields, %.1f s" % (ns, start, start + ns - 1, cpu_s),
+                               "parity_on_sample": ok}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

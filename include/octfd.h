@@ -1,0 +1,144 @@
+/*
+ * octfd.h -- C ABI of liboctfd: block finite-difference pipeline on a 2:1-balanced periodic
+ * octree of 8^3-point fp64 blocks, for one AMD MI355X (gfx950).
+ *
+ * Where the definitions come from.  The paper this library accompanies states one governing
+ * equation (inviscid Burgers, introduction, Eq. "Inviscid_Burgers" with the initial data of Eq.
+ * "initial-condition") and says only that derivatives are taken with finite-difference kernels
+ * (Sec. II-A, "Implementing the forward model") that must respect a CFL condition, suggesting
+ * higher-order stencils in Sec. V.  It defines no octree, ghost exchange, stencil order,
+ * dissipation or time integrator.  Each entry point below therefore states the textbook
+ * definition it implements.
+ *
+ * Conventions
+ *   - every function returns an int status: OT_OK (0) or a negative OT_E_* code; nothing throws,
+ *     aborts or prints.  ot_strerror() names a code, ot_last_hip_error() gives the last hipError_t.
+ *   - "host" pointers are ordinary memory; "device" pointers are HIP device memory on the current
+ *     device.  The caller owns every data array and the workspace.  The library owns only ot_tree
+ *     and the device copies of its index tables (released by octree_free).
+ *   - device entry points only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     default stream).  They do not synchronise and do not allocate, except that the first device
+ *     call on a tree (or octree_upload) copies the index tables to the device, synchronously.
+ *   - layouts (x fastest): zipped  [var][block][k][j][i]     8*8*8   doubles per block and variable
+ *                          padded  [var][block][kk][jj][ii]  14*14*14, (ii,jj,kk) = (i,j,k)+3
+ *     blocks are stored in Morton order of their anchors (x least significant bit).
+ *   - input and output arrays must not overlap, except u in rk_step.
+ */
+#ifndef OCTFD_H
+#define OCTFD_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    OT_OK = 0,
+    OT_E_BADARG = -1,      /* null pointer, size or enum out of range                    */
+    OT_E_NOMEM = -2,       /* host or device allocation failed                           */
+    OT_E_UNBALANCED = -3,  /* leaf list violates the 26-neighbour 2:1 balance            */
+    OT_E_INCOMPLETE = -4,  /* leaf list has a gap, an overlap or a duplicate             */
+    OT_E_WORKSPACE = -5,   /* workspace smaller than rk_workspace_bytes()                */
+    OT_E_HIP = -6,         /* a HIP call failed, see ot_last_hip_error()                 */
+    OT_E_NODEVICE = -7,    /* no usable GPU                                              */
+    OT_E_UNSUPPORTED = -8  /* e.g. rk_step on a kind whose input and output counts differ */
+};
+
+typedef struct ot_tree ot_tree;
+
+/* Leaf (l, ix, iy, iz) covers [i*2^-l, (i+1)*2^-l) per axis of the periodic unit cube and owns the
+ * 8^3 lattice points I = 8*i + {0..7} of the level-l lattice (N_l = 8*2^l points per axis, spacing
+ * h_l = 2^-(l+3); point I of level l coincides with point 2I of level l+1). */
+typedef struct { uint32_t level, ix, iy, iz; } ot_leaf;
+
+typedef struct {
+    uint32_t lmin, lmax;         /* 3 <= lmin <= lmax <= 19                                        */
+    uint32_t npts;               /* number of seed points                                          */
+    const uint32_t *pts_q20;     /* host, 3*npts coordinates on the 2^20 lattice                   */
+    const uint32_t *radius_q20;  /* host, lmax-lmin radii R_l for l = lmin .. lmax-1 (same lattice) */
+    uint32_t points_per_dim;     /* must be 8                                                      */
+    uint32_t pad;                /* must be 3                                                      */
+    uint32_t periodic;           /* must be 1                                                      */
+} ot_build_params;
+
+typedef enum { OT_RHS_DERIVS = 0, OT_RHS_WAVE = 1, OT_RHS_BURGERS = 2, OT_RHS_SYN24 = 3 } ot_rhs_kind;
+
+typedef struct { double ko_sigma; double reserved[7]; } ot_rhs_params;
+
+/* Tree construction (host only; works without a GPU).
+ * Start from all octants of level lmin; split an octant of level l < lmax when a seed point lies
+ * closer than R_l to its closed box (squared distance in int64 on the 2^20 lattice, minimum over
+ * the periodic images of the point, strict <); then split leaves until every leaf's 26 periodic
+ * neighbours differ from it by at most one level (the minimal such refinement is unique); order
+ * the leaves by Morton key; derive the ghost-source table.  *out receives a new tree. */
+int octree_build(const ot_build_params *params, ot_tree **out);
+
+/* Same tables from an explicit leaf list in any order.  Fails with OT_E_INCOMPLETE unless the
+ * leaves tile the cube exactly once, with OT_E_UNBALANCED unless they are 26-balanced. */
+int octree_from_leaves(const ot_leaf *leaves, size_t n, uint32_t pad, ot_tree **out);
+
+int octree_num_blocks(const ot_tree *tree, int64_t *nb);
+
+/* Copies the leaves, in storage (Morton) order, to host array out[cap]; cap >= number of blocks. */
+int octree_get_leaves(const ot_tree *tree, ot_leaf *out, size_t cap);
+
+/* Ghost-source table, host array out[cap] of int32, cap >= nb*27*5.  Entry [b][d][0..4] describes
+ * the part of block b's padded box in direction d = (dz+1)*9 + (dy+1)*3 + (dx+1), d* in {-1,0,1}:
+ * [0] = 0 same level, 1 finer, 2 coarser; [1..4] = source block ids in ascending order, -1 filled
+ * (finer: 4 ids across a face, 2 along an edge, 1 at a corner).  Entry d = 13 is the block itself. */
+int octree_get_ghost_table(const ot_tree *tree, int32_t *out, size_t cap);
+
+/* Copies the index tables to the current device now (otherwise done by the first device call). */
+int octree_upload(ot_tree *tree);
+
+int octree_free(ot_tree *tree); /* NULL is allowed */
+
+/* Number of variables a kind reads / writes: DERIVS 1/4, WAVE 2/2, BURGERS 1/1, SYN24 24/24. */
+int ot_rhs_nvar_in(ot_rhs_kind kind);
+int ot_rhs_nvar_out(ot_rhs_kind kind);
+
+/* unzip: zipped_dev [nvar][nb][8^3] -> padded_dev [nvar][nb][14^3].
+ * Each padded point is lattice point P = 8a + (ii,jj,kk) - 3 (mod N_l) of the block's level and
+ * receives the value held by the leaf that contains it: a copy from a leaf of the same level, an
+ * injection (fine index 2P - 8a') from a finer leaf, or, from a coarser leaf, per axis with
+ * f = P - 16a' in [0,16): node f/2 if f is even, else 6-point Lagrange interpolation on that
+ * leaf's own nodes s..s+5, s = clamp((f-1)/2 - 2, 0, 2).  Axes are interpolated in the order
+ * x, y, z, each as acc = w0*v0, acc = fma(w_m, v_m, acc). */
+int unzip(ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev, void *hip_stream);
+
+/* rhs_eval: padded_dev [nvar_in][nb][14^3] -> rhs_padded_dev [nvar_out][nb][14^3]; only the 8^3
+ * interior of each output block is written.  Sixth-order centred first and second derivatives,
+ * mixed derivatives as D1_a(D1_b u), sixth-difference Kreiss-Oliger dissipation with strength
+ * ko_sigma fused into the same pass.
+ *   DERIVS : (D_x u, D_y u, D_z u, Laplacian u), no dissipation
+ *   WAVE   : d_t u = pi + KO(u);  d_t pi = Laplacian u + KO(pi)
+ *   BURGERS: d_t u = KO(u) - u D_x u            (the paper's equation, flux along x)
+ *   SYN24  : 24-field synthetic system with 72 first and 60 second derivatives. */
+int rhs_eval(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
+             const double *padded_dev, double *rhs_padded_dev, void *hip_stream);
+
+/* zip: padded_dev [nvar][nb][14^3] -> zipped_dev [nvar][nb][8^3]; drops the ghost layers. */
+int zip(ot_tree *tree, int nvar, const double *padded_dev, double *zipped_dev, void *hip_stream);
+
+/* The three calls above fused: zipped in, zipped right-hand side out, no padded array in memory.
+ * Bit-identical to zip(rhs_eval(unzip(.))). */
+int rhs_eval_zipped(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
+                    const double *zipped_dev, double *rhs_zipped_dev, void *hip_stream);
+
+/* Classical fourth-order Runge-Kutta step of d_t u = F(u), F = zip(rhs_eval(unzip(.))):
+ *   k1 = F(u), k2 = F(u + dt/2 k1), k3 = F(u + dt/2 k2), k4 = F(u + dt k3),
+ *   u <- u + dt/6 (((k1 + 2 k2) + 2 k3) + k4),  every a*k + u evaluated as one fma.
+ * u_zipped_dev [nvar][nb][8^3] is updated in place.  workspace_dev must hold at least
+ * rk_workspace_bytes() bytes (three zipped state vectors) and be 256-byte aligned. */
+int rk_workspace_bytes(const ot_tree *tree, ot_rhs_kind kind, size_t *bytes);
+int rk_step(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,
+            double *u_zipped_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+const char *ot_strerror(int status);
+int ot_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OCTFD_H */

@@ -1,0 +1,254 @@
+// C ABI of liboctfd (see include/octfd.h): argument checking, tree ownership, lazy upload of the
+// index tables, and the sequencing of kernel launches.  No arithmetic of the method lives here.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <new>
+
+#include "kernels.hpp"
+#include "octfd.h"
+#include "octree_host.hpp"
+
+using namespace octfd;
+
+struct ot_tree {
+    HostTree host;
+    ot_leaf* d_leaves = nullptr;
+    int32_t* d_ghost = nullptr;
+    int device = -1;   // device the tables live on, -1 = not uploaded
+};
+
+namespace {
+
+std::atomic<int> g_last_hip{0};
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip.store(static_cast<int>(e));
+    return (e == hipErrorNoDevice || e == hipErrorInvalidDevice || e == hipErrorInsufficientDriver) ? OT_E_NODEVICE
+           : (e == hipErrorOutOfMemory)                                                             ? OT_E_NOMEM
+                                                                                                    : OT_E_HIP;
+}
+
+int ensure_device(ot_tree* t)
+{
+    if (t->device >= 0) return OT_OK;
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (ndev <= 0) return OT_E_NODEVICE;
+    int dev = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e);
+    const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
+    if ((e = hipMalloc(reinterpret_cast<void**>(&t->d_leaves), nl)) != hipSuccess) return hip_fail(e);
+    if ((e = hipMalloc(reinterpret_cast<void**>(&t->d_ghost), ng)) != hipSuccess) {
+        (void)hipFree(t->d_leaves); t->d_leaves = nullptr;
+        return hip_fail(e);
+    }
+    e = hipMemcpy(t->d_leaves, t->host.leaves.data(), nl, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(t->d_ghost, t->host.ghost.data(), ng, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(t->d_leaves); (void)hipFree(t->d_ghost);
+        t->d_leaves = nullptr; t->d_ghost = nullptr;
+        return hip_fail(e);
+    }
+    t->device = dev;
+    return OT_OK;
+}
+
+DeviceTree dev_view(const ot_tree* t)
+{
+    return DeviceTree{t->d_leaves, t->d_ghost, static_cast<int64_t>(t->host.leaves.size())};
+}
+
+bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }
+
+}  // namespace
+
+extern "C" {
+
+int octree_build(const ot_build_params* params, ot_tree** out)
+{
+    if (!params || !out) return OT_E_BADARG;
+    *out = nullptr;
+    ot_tree* t = new (std::nothrow) ot_tree;
+    if (!t) return OT_E_NOMEM;
+    int rc;
+    try { rc = build_tree(*params, t->host); } catch (const std::bad_alloc&) { rc = OT_E_NOMEM; }
+    if (rc != OT_OK) { delete t; return rc; }
+    *out = t;
+    return OT_OK;
+}
+
+int octree_from_leaves(const ot_leaf* leaves, size_t n, uint32_t pad, ot_tree** out)
+{
+    if (!leaves || !out || n == 0) return OT_E_BADARG;
+    *out = nullptr;
+    if (pad != 3) return OT_E_UNSUPPORTED;
+    ot_tree* t = new (std::nothrow) ot_tree;
+    if (!t) return OT_E_NOMEM;
+    int rc;
+    try { rc = tree_from_leaves(leaves, n, t->host); } catch (const std::bad_alloc&) { rc = OT_E_NOMEM; }
+    if (rc != OT_OK) { delete t; return rc; }
+    *out = t;
+    return OT_OK;
+}
+
+int octree_num_blocks(const ot_tree* tree, int64_t* nb)
+{
+    if (!tree || !nb) return OT_E_BADARG;
+    *nb = static_cast<int64_t>(tree->host.leaves.size());
+    return OT_OK;
+}
+
+int octree_get_leaves(const ot_tree* tree, ot_leaf* out, size_t cap)
+{
+    if (!tree || !out || cap < tree->host.leaves.size()) return OT_E_BADARG;
+    for (size_t i = 0; i < tree->host.leaves.size(); ++i) out[i] = tree->host.leaves[i];
+    return OT_OK;
+}
+
+int octree_get_ghost_table(const ot_tree* tree, int32_t* out, size_t cap)
+{
+    if (!tree || !out || cap < tree->host.ghost.size()) return OT_E_BADARG;
+    for (size_t i = 0; i < tree->host.ghost.size(); ++i) out[i] = tree->host.ghost[i];
+    return OT_OK;
+}
+
+int octree_upload(ot_tree* tree)
+{
+    if (!tree) return OT_E_BADARG;
+    return ensure_device(tree);
+}
+
+int octree_free(ot_tree* tree)
+{
+    if (!tree) return OT_OK;
+    int rc = OT_OK;
+    if (tree->device >= 0) {
+        hipError_t e = hipFree(tree->d_leaves);
+        hipError_t f = hipFree(tree->d_ghost);
+        if (e != hipSuccess) rc = hip_fail(e);
+        else if (f != hipSuccess) rc = hip_fail(f);
+    }
+    delete tree;
+    return rc;
+}
+
+int ot_rhs_nvar_in(ot_rhs_kind kind)
+{
+    switch (kind) {
+    case OT_RHS_DERIVS: return 1;
+    case OT_RHS_WAVE: return 2;
+    case OT_RHS_BURGERS: return 1;
+    case OT_RHS_SYN24: return 24;
+    default: return OT_E_BADARG;
+    }
+}
+
+int ot_rhs_nvar_out(ot_rhs_kind kind)
+{
+    switch (kind) {
+    case OT_RHS_DERIVS: return 4;
+    case OT_RHS_WAVE: return 2;
+    case OT_RHS_BURGERS: return 1;
+    case OT_RHS_SYN24: return 24;
+    default: return OT_E_BADARG;
+    }
+}
+
+int unzip(ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
+{
+    if (!tree || nvar <= 0 || nvar > 65535 || !zipped_dev || !padded_dev) return OT_E_BADARG;
+    if (int rc = ensure_device(tree)) return rc;
+    hipError_t e = launch_unzip(dev_view(tree), nvar, zipped_dev, padded_dev, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OT_OK : hip_fail(e);
+}
+
+int zip(ot_tree* tree, int nvar, const double* padded_dev, double* zipped_dev, void* hip_stream)
+{
+    if (!tree || nvar <= 0 || !zipped_dev || !padded_dev) return OT_E_BADARG;
+    if (int rc = ensure_device(tree)) return rc;
+    hipError_t e = launch_zip(dev_view(tree), nvar, padded_dev, zipped_dev, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OT_OK : hip_fail(e);
+}
+
+int rhs_eval(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, const double* padded_dev,
+             double* rhs_padded_dev, void* hip_stream)
+{
+    if (!tree || !kind_ok(kind) || !params || !padded_dev || !rhs_padded_dev) return OT_E_BADARG;
+    if (int rc = ensure_device(tree)) return rc;
+    RhsArgs a{padded_dev, rhs_padded_dev, nullptr, nullptr, 0.0, params->ko_sigma};
+    hipError_t e = launch_rhs(dev_view(tree), kind, false, kOutPadded, a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OT_OK : hip_fail(e);
+}
+
+int rhs_eval_zipped(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, const double* zipped_dev,
+                    double* rhs_zipped_dev, void* hip_stream)
+{
+    if (!tree || !kind_ok(kind) || !params || !zipped_dev || !rhs_zipped_dev) return OT_E_BADARG;
+    if (int rc = ensure_device(tree)) return rc;
+    RhsArgs a{zipped_dev, rhs_zipped_dev, nullptr, nullptr, 0.0, params->ko_sigma};
+    hipError_t e = launch_rhs(dev_view(tree), kind, true, kOutZipped, a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OT_OK : hip_fail(e);
+}
+
+int rk_workspace_bytes(const ot_tree* tree, ot_rhs_kind kind, size_t* bytes)
+{
+    if (!tree || !kind_ok(kind) || !bytes) return OT_E_BADARG;
+    if (ot_rhs_nvar_in(kind) != ot_rhs_nvar_out(kind)) return OT_E_UNSUPPORTED;
+    *bytes = 3 * static_cast<size_t>(ot_rhs_nvar_in(kind)) * tree->host.leaves.size() * 512 * sizeof(double);
+    return OT_OK;
+}
+
+int rk_step(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u_zipped_dev,
+            void* workspace_dev, size_t workspace_bytes, void* hip_stream)
+{
+    if (!tree || !kind_ok(kind) || !params || !u_zipped_dev || !workspace_dev) return OT_E_BADARG;
+    size_t need = 0;
+    if (int rc = rk_workspace_bytes(tree, kind, &need)) return rc;
+    if (workspace_bytes < need) return OT_E_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % 256) return OT_E_BADARG;
+    if (int rc = ensure_device(tree)) return rc;
+    const size_t len = need / (3 * sizeof(double));
+    double* acc = static_cast<double*>(workspace_dev);
+    double* sa = acc + len;
+    double* sb = sa + len;
+    double* u = u_zipped_dev;
+    const DeviceTree dv = dev_view(tree);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const double sg = params->ko_sigma;
+    // stage vectors ping-pong between sa and sb: a stage reads ghosts of the vector it was given
+    // while writing the next one, so the two must be different arrays
+    const RhsArgs st[4] = {
+        {u, sa, acc, u, 0.5 * dt, sg},    // k1 = F(u):   acc = k1,        sa = u + dt/2 k1
+        {sa, sb, acc, u, 0.5 * dt, sg},   // k2 = F(sa):  acc += 2 k2,     sb = u + dt/2 k2
+        {sb, sa, acc, u, dt, sg},         // k3 = F(sb):  acc += 2 k3,     sa = u + dt k3
+        {sa, nullptr, acc, u, dt / 6.0, sg}};   // k4 = F(sa):  u += dt/6 (acc + k4)
+    const Epilogue ep[4] = {kRkFirst, kRkMiddle, kRkMiddle, kRkLast};
+    for (int i = 0; i < 4; ++i) {
+        hipError_t e = launch_rhs(dv, kind, true, ep[i], st[i], s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return OT_OK;
+}
+
+const char* ot_strerror(int status)
+{
+    switch (status) {
+    case OT_OK: return "ok";
+    case OT_E_BADARG: return "bad argument";
+    case OT_E_NOMEM: return "out of memory";
+    case OT_E_UNBALANCED: return "leaves are not 2:1 balanced over the 26 neighbours";
+    case OT_E_INCOMPLETE: return "leaves do not tile the cube exactly once";
+    case OT_E_WORKSPACE: return "workspace too small";
+    case OT_E_HIP: return "HIP call failed";
+    case OT_E_NODEVICE: return "no usable GPU";
+    case OT_E_UNSUPPORTED: return "unsupported parameter";
+    default: return "unknown status";
+    }
+}
+
+int ot_last_hip_error(void) { return g_last_hip.load(); }
+
+}  // extern "C"

@@ -1,0 +1,41 @@
+// Launch interface between the C ABI (capi.cpp) and the gfx950 kernels (kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "octfd.h"
+
+namespace octfd {
+
+struct DeviceTree {
+    const ot_leaf* leaves;   // [nb]
+    const int32_t* ghost;    // [nb][27][5]
+    int64_t nb;
+};
+
+// how the right-hand side leaves the kernel
+enum Epilogue : int {
+    kOutPadded = 0,   // interior of a padded-shaped array
+    kOutZipped = 1,   // zipped array
+    kRkFirst = 2,     // acc = k;        stage = fma(c, k, u)        (u is the kernel's input)
+    kRkMiddle = 3,    // acc = acc + 2k; stage = fma(c, k, u)
+    kRkLast = 4       // u = fma(c, acc + k, u)
+};
+
+struct RhsArgs {
+    const double* in;   // padded [V][nb][2744] or zipped [V][nb][512]
+    double* out;        // kOutPadded / kOutZipped: result; kRkFirst / kRkMiddle: next stage vector
+    double* acc;        // Runge-Kutta accumulator (zipped)
+    double* u;          // state at the start of the step (zipped); written by kRkLast
+    double c;           // dt/2, dt or dt/6
+    double sigma;       // Kreiss-Oliger strength
+};
+
+hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, double* padded, hipStream_t s);
+hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, double* zipped, hipStream_t s);
+// in_zipped = false: args.in is padded (then ep must be kOutPadded); true: args.in is zipped
+hipError_t launch_rhs(const DeviceTree& t, ot_rhs_kind kind, bool in_zipped, Epilogue ep, const RhsArgs& args,
+                      hipStream_t s);
+
+}  // namespace octfd

@@ -1,0 +1,24 @@
+// Host-side octree engine of liboctfd: pointer octree, queue-driven 2:1 balance, Morton-order
+// traversal and the ghost-source table.  No device code here.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "octfd.h"
+
+namespace octfd {
+
+constexpr int kDirs = 27;          // directions (dz+1)*9 + (dy+1)*3 + (dx+1)
+constexpr int kEntry = 5;          // {kind, id0..id3}
+enum GhostKind : int32_t { kSame = 0, kFiner = 1, kCoarser = 2 };
+
+struct HostTree {
+    std::vector<ot_leaf> leaves;   // Morton order
+    std::vector<int32_t> ghost;    // [nb][27][5]
+};
+
+// Each returns an OT_* status.
+int build_tree(const ot_build_params& p, HostTree& out);
+int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out);
+
+}  // namespace octfd

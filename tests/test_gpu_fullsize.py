@@ -1,0 +1,54 @@
+"""Parity at the benchmark's full size (the ~1e5-block, 24-field tree) in the launch configuration
+bench.py times: the fused right-hand side on sampled blocks against the oracle, and rk_step against
+its own definition composed from calls that are themselves checked against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2007_12792_amd as octfd
+import synthdata as sd
+from test_gpu_parity import assert_close, dev, dev_empty  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config5_rhs_sampled_and_rk_step(orc, dev):  # noqa: F811
+    p = sd.tree_params("C5")
+    to, tg = orc.Tree.build(**p), octfd.Tree.build(**p)
+    assert tg.n == 102075
+    print("generating fields", flush=True)
+    ud = sd.make_fields("C5", to.leaves, device=dev)
+    sg, dt = sd.KO_SIGMA, sd.time_step(9)
+    k1 = dev_empty((24, tg.n, 8, 8, 8), dev)
+    tg.rhs_eval_zipped(3, ud, k1, sigma=sg)
+    torch.cuda.synchronize()
+    print("rhs done", flush=True)
+    lev = to.leaves[:, 0]
+    coarse = np.flatnonzero(lev < 9)
+    sample = np.unique(np.concatenate([np.arange(0, tg.n, 1501), coarse[::97], [0, tg.n - 1]]))
+    u = ud.cpu().numpy()
+    want = to.F(3, u, sigma=sg, blocks=sample)
+    del u
+    sel = torch.from_numpy(sample).to(dev)
+    assert_close(k1[:, sel].cpu().numpy(), want, "C5 rhs_eval_zipped, %d sampled blocks" % sample.size)
+    # rk_step == the tableau written with the library's F (checked above) and torch vector ops.
+    # dt is a power of two, so u + c*k is exact-product-then-add = one fma; only the last line's
+    # dt/6 is not, which costs at most one rounding of difference.
+    F = lambda v, out: tg.rhs_eval_zipped(3, v, out, sigma=sg)
+    k = dev_empty((24, tg.n, 8, 8, 8), dev)
+    st = ud + (0.5 * dt) * k1
+    acc = k1.clone()
+    F(st, k); acc += 2.0 * k; st = ud + (0.5 * dt) * k
+    F(st, k); acc += 2.0 * k; st = ud + dt * k
+    F(st, k); acc += k
+    want_u = ud + (dt / 6.0) * acc
+    del st, k, k1
+    ws = torch.empty(tg.rk_workspace_bytes(3) // 8, dtype=torch.float64, device=dev)
+    got = ud.clone()
+    tg.rk_step(3, got, dt, ws, sigma=sg)
+    torch.cuda.synchronize()
+    err = (got - want_u).abs()
+    bound = 1e-12 * want_u.abs() + 1e-13
+    print("rk_step C5: worst |diff|/bound = %.3g" % float((err / bound).max()), flush=True)
+    assert bool((err <= bound).all())
+    assert float((got - ud).abs().max()) > 0

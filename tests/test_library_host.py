@@ -1,0 +1,124 @@
+"""Host-side checks of liboctfd that need no GPU: exported symbols, tree and ghost table bit-exact
+against the oracle, error paths."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2007_12792_amd as octfd
+import synthdata as sd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "octfd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(?:int|const char \*)\s*\**\s*(\w+)\s*\(", header))
+    assert declared == set(octfd.EXPORTS)
+    L = C.CDLL(octfd.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("name", ["C1", "T2", "T4", "C2", "C4", "C3", "C5"])
+def test_tree_and_ghost_table_bit_exact(orc, name):
+    p = sd.tree_params(name)
+    a = orc.Tree.build(**p)
+    b = octfd.Tree.build(**p)
+    assert b.n == a.n
+    assert (b.leaves == a.leaves).all()
+    if a.n <= 25000:      # the oracle locates 2,744 points per block: keep the CPU suite short
+        assert (b.ghost_table() == a.ghost_table()).all()
+
+
+def test_ghost_table_bit_exact_on_sampled_blocks_of_the_largest_tree(orc):
+    # the oracle's table is all-or-nothing, so compare through a sub-tree-independent property
+    # instead: for sampled blocks of C5, every table entry must name exactly the leaves that the
+    # oracle's point location finds in that part of the padded box (checked through unzip of a
+    # field that stores each block's own index).
+    p = sd.tree_params("C5")
+    a = orc.Tree.build(**p)
+    b = octfd.Tree.build(**p)
+    ids = np.broadcast_to(np.arange(a.n, dtype=np.float64)[:, None, None, None], (a.n, 8, 8, 8))[None]
+    sample = np.arange(0, a.n, 997)
+    pad = a.unzip(ids, blocks=sample)[0]            # interpolating a constant-per-leaf field returns it
+    g = b.ghost_table()[sample]
+    lo = {0: (0, 3), 1: (3, 11), 2: (11, 14)}
+    for s in range(sample.size):
+        for d in range(27):
+            rx, ry, rz = d % 3, (d // 3) % 3, d // 9
+            reg = pad[s, lo[rz][0]:lo[rz][1], lo[ry][0]:lo[ry][1], lo[rx][0]:lo[rx][1]]
+            found = sorted(set(np.rint(reg).astype(np.int64).ravel().tolist()))
+            want = sorted(i for i in g[s, d, 1:].tolist() if i >= 0)
+            assert found == want, (sample[s], d)
+            lev = a.leaves[found[0], 0].astype(int) - a.leaves[sample[s], 0].astype(int)
+            assert g[s, d, 0] == {0: 0, 1: 1, -1: 2}[lev]
+
+
+def test_from_leaves_round_trip_and_errors(orc):
+    p = sd.tree_params("T4")
+    t = octfd.Tree.build(**p)
+    lv = t.leaves
+    rng = np.random.default_rng(0)
+    again = octfd.Tree.from_leaves(lv[rng.permutation(t.n)])
+    assert (again.leaves == lv).all() and (again.ghost_table() == t.ghost_table()).all()
+    with pytest.raises(octfd.OctfdError) as e:
+        octfd.Tree.from_leaves(lv[:-1])
+    assert e.value.status == octfd.OT_E_INCOMPLETE
+    with pytest.raises(octfd.OctfdError) as e:
+        octfd.Tree.from_leaves(np.vstack([lv, lv[:1]]))
+    assert e.value.status == octfd.OT_E_INCOMPLETE
+    # replace one complete sibling octet deep inside the fine region by its parent
+    fine = lv[lv[:, 0] == lv[:, 0].max()].astype(np.int64)
+    S = {tuple(r) for r in lv.astype(np.int64).tolist()}
+    for l, x, y, z in fine.tolist():
+        if (x | y | z) & 1:
+            continue
+        sibs = {(l, x + (c & 1), y + ((c >> 1) & 1), z + ((c >> 2) & 1)) for c in range(8)}
+        if sibs <= S:
+            trial = np.array(sorted((S - sibs) | {(l - 1, x >> 1, y >> 1, z >> 1)}), dtype=np.uint32)
+            try:
+                orc.Tree.from_leaves(trial)
+                oracle_ok = True
+            except ValueError:
+                oracle_ok = False
+            if oracle_ok:
+                octfd.Tree.from_leaves(trial)
+            else:
+                with pytest.raises(octfd.OctfdError) as e:
+                    octfd.Tree.from_leaves(trial)
+                assert e.value.status == octfd.OT_E_UNBALANCED
+    # unbalanced by construction: one level-5 octet inside a level-3 tree
+    base = [(3, x, y, z) for z in range(8) for y in range(8) for x in range(8) if (x, y, z) != (0, 0, 0)]
+    kids4 = [(4, cx, cy, cz) for cz in range(2) for cy in range(2) for cx in range(2) if (cx, cy, cz) != (0, 0, 0)]
+    kids5 = [(5, cx, cy, cz) for cz in range(2) for cy in range(2) for cx in range(2)]
+    with pytest.raises(octfd.OctfdError) as e:
+        octfd.Tree.from_leaves(np.array(base + kids4 + kids5, dtype=np.uint32))
+    assert e.value.status == octfd.OT_E_UNBALANCED
+
+
+def test_bad_arguments_are_reported_not_crashed():
+    L = octfd.lib()
+    assert L.octree_build(None, None) == octfd.OT_E_BADARG
+    h = C.c_void_p()
+    p = octfd.BuildParams(2, 3, 0, None, None, 8, 3, 1)          # lmin < 3
+    assert L.octree_build(C.byref(p), C.byref(h)) == octfd.OT_E_BADARG
+    p = octfd.BuildParams(3, 3, 0, None, None, 8, 2, 1)          # pad != 3
+    assert L.octree_build(C.byref(p), C.byref(h)) == octfd.OT_E_UNSUPPORTED
+    assert L.octree_free(None) == octfd.OT_OK
+    assert L.ot_rhs_nvar_in(7) == octfd.OT_E_BADARG
+    assert [octfd.nvar_in(k) for k in range(4)] == [1, 2, 1, 24]
+    assert [octfd.nvar_out(k) for k in range(4)] == [4, 2, 1, 24]
+    t = octfd.Tree.build(3, 3, np.zeros((0, 3), np.uint32), np.zeros(0, np.uint32))
+    assert t.n == 512
+    n = C.c_size_t()
+    assert L.rk_workspace_bytes(t._h, octfd.DERIVS, C.byref(n)) == octfd.OT_E_UNSUPPORTED
+    assert t.rk_workspace_bytes(octfd.WAVE) == 3 * 2 * 512 * 512 * 8
+    assert L.unzip(t._h, 1, None, None, None) == octfd.OT_E_BADARG
+    one = C.c_void_p(256)
+    rp = octfd.RhsParams(0.4)
+    assert L.rk_step(t._h, octfd.WAVE, C.byref(rp), 0.1, one, one, 16, None) == octfd.OT_E_WORKSPACE
+    assert octfd.strerror(octfd.OT_E_WORKSPACE) == "workspace too small"

@@ -15,6 +15,7 @@ struct ot_tree {
     HostTree host;
     ot_leaf* d_leaves = nullptr;
     int32_t* d_ghost = nullptr;
+    int32_t* d_coarse = nullptr;
     int device = -1;   // device the tables live on, -1 = not uploaded
 };
 
@@ -39,26 +40,31 @@ int ensure_device(ot_tree* t)
     if (ndev <= 0) return OT_E_NODEVICE;
     int dev = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e);
+    // kernels index one variable's zipped array with 32-bit offsets
+    if (t->host.leaves.size() * 512 >= (size_t(1) << 31)) return OT_E_UNSUPPORTED;
     const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
-    if ((e = hipMalloc(reinterpret_cast<void**>(&t->d_leaves), nl)) != hipSuccess) return hip_fail(e);
-    if ((e = hipMalloc(reinterpret_cast<void**>(&t->d_ghost), ng)) != hipSuccess) {
-        (void)hipFree(t->d_leaves); t->d_leaves = nullptr;
-        return hip_fail(e);
-    }
-    e = hipMemcpy(t->d_leaves, t->host.leaves.data(), nl, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(t->d_ghost, t->host.ghost.data(), ng, hipMemcpyHostToDevice);
+    const size_t nc = t->host.coarse.size() * sizeof(int32_t);
+    // one allocation for the three tables, each part 256-byte aligned
+    const size_t ol = 0, og = (nl + 255) / 256 * 256, oc = og + (ng + 255) / 256 * 256;
+    char* base = nullptr;
+    if ((e = hipMalloc(reinterpret_cast<void**>(&base), oc + nc)) != hipSuccess) return hip_fail(e);
+    e = hipMemcpy(base + ol, t->host.leaves.data(), nl, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(base + og, t->host.ghost.data(), ng, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(base + oc, t->host.coarse.data(), nc, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
-        (void)hipFree(t->d_leaves); (void)hipFree(t->d_ghost);
-        t->d_leaves = nullptr; t->d_ghost = nullptr;
+        (void)hipFree(base);
         return hip_fail(e);
     }
+    t->d_leaves = reinterpret_cast<ot_leaf*>(base + ol);
+    t->d_ghost = reinterpret_cast<int32_t*>(base + og);
+    t->d_coarse = reinterpret_cast<int32_t*>(base + oc);
     t->device = dev;
     return OT_OK;
 }
 
 DeviceTree dev_view(const ot_tree* t)
 {
-    return DeviceTree{t->d_leaves, t->d_ghost, static_cast<int64_t>(t->host.leaves.size())};
+    return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, static_cast<int64_t>(t->host.leaves.size())};
 }
 
 bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }
@@ -126,10 +132,8 @@ int octree_free(ot_tree* tree)
     if (!tree) return OT_OK;
     int rc = OT_OK;
     if (tree->device >= 0) {
-        hipError_t e = hipFree(tree->d_leaves);
-        hipError_t f = hipFree(tree->d_ghost);
+        hipError_t e = hipFree(tree->d_leaves);   // the tables share one allocation
         if (e != hipSuccess) rc = hip_fail(e);
-        else if (f != hipSuccess) rc = hip_fail(f);
     }
     delete tree;
     return rc;

@@ -159,6 +159,43 @@ int make_ghost_table(const Octree& t, const std::vector<ot_leaf>& leaves, std::v
 
 }  // namespace
 
+// A coarser leaf is a cube and the padded block a box, so the padded points one coarser leaf
+// supplies form a box: the product of per-axis ranges of the three parts {ghost-low, interior,
+// ghost-high}.  A block in the corner of its parent touches at most seven coarser leaves.
+void make_coarse_sources(HostTree& t)
+{
+    const size_t nb = t.leaves.size();
+    t.coarse.assign(nb * 16, -1);
+    for (size_t b = 0; b < nb; ++b) {
+        int32_t* out = &t.coarse[b * 16];
+        int n = 0;
+        int32_t ids[8];
+        int lo[8][3], hi[8][3];
+        for (int dir = 0; dir < kDirs; ++dir) {
+            const int32_t* e = &t.ghost[(b * kDirs + dir) * kEntry];
+            if (e[0] != kCoarser) continue;
+            const int r[3] = {dir % 3, (dir / 3) % 3, dir / 9};
+            int s = 0;
+            while (s < n && ids[s] != e[1]) ++s;
+            if (s == n) {
+                if (n == 8) continue;  // cannot happen on a balanced tree
+                ids[n] = e[1];
+                for (int ax = 0; ax < 3; ++ax) lo[n][ax] = hi[n][ax] = r[ax];
+                ++n;
+            } else {
+                for (int ax = 0; ax < 3; ++ax) {
+                    if (r[ax] < lo[s][ax]) lo[s][ax] = r[ax];
+                    if (r[ax] > hi[s][ax]) hi[s][ax] = r[ax];
+                }
+            }
+        }
+        for (int s = 0; s < n; ++s) {
+            out[2 * s] = ids[s];
+            out[2 * s + 1] = lo[s][0] | (hi[s][0] << 2) | (lo[s][1] << 4) | (hi[s][1] << 6) | (lo[s][2] << 8) | (hi[s][2] << 10);
+        }
+    }
+}
+
 int build_tree(const ot_build_params& p, HostTree& out)
 {
     if (p.lmin < 3 || p.lmax < p.lmin || p.lmax > 19) return OT_E_BADARG;
@@ -184,7 +221,9 @@ int build_tree(const ot_build_params& p, HostTree& out)
     balance(t, leaves_to_balance);
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
-    return make_ghost_table(t, out.leaves, out.ghost);
+    const int rc = make_ghost_table(t, out.leaves, out.ghost);
+    if (rc == OT_OK) make_coarse_sources(out);
+    return rc;
 }
 
 int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out)
@@ -209,7 +248,9 @@ int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out)
         if (nd.first_child == kUnset) return OT_E_INCOMPLETE;                // a gap
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
-    return make_ghost_table(t, out.leaves, out.ghost);
+    const int rc = make_ghost_table(t, out.leaves, out.ghost);
+    if (rc == OT_OK) make_coarse_sources(out);
+    return rc;
 }
 
 }  // namespace octfd

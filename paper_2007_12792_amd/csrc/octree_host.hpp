@@ -15,10 +15,16 @@ enum GhostKind : int32_t { kSame = 0, kFiner = 1, kCoarser = 2 };
 struct HostTree {
     std::vector<ot_leaf> leaves;   // Morton order
     std::vector<int32_t> ghost;    // [nb][27][5]
+    // Derived from `ghost` for the kernels: the distinct coarser source leaves of every block, each
+    // with the box of the padded block it covers.  [nb][8][2] = {leaf id, packed ranges}, id -1
+    // ends the list; packed = xlo | xhi<<2 | ylo<<4 | yhi<<6 | zlo<<8 | zhi<<10 with 0/1/2 naming
+    // the ghost-low, interior and ghost-high part of an axis (inclusive ranges).
+    std::vector<int32_t> coarse;
 };
 
 // Each returns an OT_* status.
 int build_tree(const ot_build_params& p, HostTree& out);
 int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out);
+void make_coarse_sources(HostTree& t);
 
 }  // namespace octfd

@@ -40,8 +40,8 @@ int ensure_device(ot_tree* t)
     if (ndev <= 0) return OT_E_NODEVICE;
     int dev = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e);
-    // kernels index one variable's zipped array with 32-bit offsets
-    if (t->host.leaves.size() * 512 >= (size_t(1) << 31)) return OT_E_UNSUPPORTED;
+    // kernels address one variable's zipped array with 32-bit byte offsets
+    if (t->host.leaves.size() >= (size_t(1) << 20)) return OT_E_UNSUPPORTED;
     const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
     const size_t nc = t->host.coarse.size() * sizeof(int32_t);
     // one allocation for the three tables, each part 256-byte aligned

@@ -23,16 +23,24 @@ constexpr int NPT = 8, PAD = 3, NP = 14, BLK = 512, PBLK = 2744;
 constexpr int NTHREADS = 512;
 constexpr int K_COARSER = 2, K_SAME = 0;
 
-// LDS geometry (in doubles).  Row stride 16 and plane stride 8 (mod 32) make the eight x-contiguous
-// values of the four (j,k) pairs held by one half-wavefront fall into 32 different 8-byte banks.
-constexpr int RS = 16;
-constexpr int PS = NP * RS + 8;          // 232
+// LDS geometry (in doubles).  Rows are stored compactly (stride 14) and planes are padded to a
+// stride of 200 = 8 (mod 32).  A wavefront holds one j row of the block, its lanes run over
+// (i, k): the eight x-contiguous values of four consecutive k planes then fall into 32 different
+// 8-byte banks, and shifting the access by any stencil offset keeps that property.
+#ifndef OCTFD_SKIP
+#define OCTFD_SKIP 0   // timing experiments: 1 = no mixed derivatives, 2 = no global loads, 4 = no stencils, 8 = no stores
+#endif
+#ifndef OCTFD_WAVES_PER_SIMD
+#define OCTFD_WAVES_PER_SIMD 4
+#endif
+constexpr int RS = NP;                   // 14
+constexpr int PS = NP * RS + 4;          // 200
 constexpr int TILE = NP * PS;            // 14 planes
 constexpr int WZ = NPT * PS;             // D1_z u on [8 k][14 jj][14 ii]
-constexpr int YPS = NPT * RS + 8;        // plane stride of the D1_y array, 136
+constexpr int YPS = NPT * RS + 8;        // plane stride of the D1_y array, 120 = 24 (mod 32)
 constexpr int WY = NPT * YPS;            // D1_y u on [8 k][8 j][14 ii]
 constexpr int T1N = 64 * NP, T2N = NPT * NP * NP;            // interpolation staging
-constexpr int SCRATCH = (WZ + WY) > (BLK + T1N + T2N) ? (WZ + WY) : (BLK + T1N + T2N);
+constexpr int SCRATCH = (WZ + WY) > (T1N + T2N) ? (WZ + WY) : (T1N + T2N);   // the coarse leaf C overlays T2
 
 // six-point Lagrange weights on nodes 0..5 at r = 1/2, 3/2, ..., 11/2 (numerators over 256)
 __constant__ double c_lag[36] = {
@@ -52,14 +60,40 @@ struct BlockInfo {       // per-workgroup copy of the block's table rows
 
 __device__ __forceinline__ int tidx(int kk, int jj, int ii) { return kk * PS + jj * RS + ii; }
 
-// thread -> interior point.  Lane bits 0-2 = i, bit 3 = j0, bit 4 = k0, bit 5 = j1; the wavefront
-// number supplies j2 and k1, k2.  A half-wavefront thus covers 8 x 2 x 2 points.
+// thread -> interior point: lanes run over (i, k), the wavefront number is j.
 __device__ __forceinline__ void point_of(int tid, int& i, int& j, int& k)
 {
-    const int w = tid >> 6;
     i = tid & 7;
-    j = ((tid >> 3) & 1) | (((tid >> 5) & 1) << 1) | ((w & 1) << 2);
-    k = ((tid >> 4) & 1) | ((w >> 1) << 1);
+    k = (tid >> 3) & 7;
+    j = tid >> 6;
+}
+
+// Loads and stores of global arrays use a uniform 64-bit base (one variable's array) plus a 32-bit
+// byte offset held per thread, so that no per-access 64-bit address arithmetic is needed.  The
+// library refuses trees with 2^20 blocks or more, which keeps every offset below 2^32.
+// The empty asm keeps the 32-bit offset a 32-bit register at the point of use; otherwise the
+// compiler widens the offsets to 64 bits once, outside the variable loop, which doubles their
+// register cost and forces a 64-bit add per access.
+__device__ __forceinline__ double ldg(const double* base, uint32_t byte_off)
+{
+    asm volatile("" : "+v"(byte_off));
+    return *reinterpret_cast<const double*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+__device__ __forceinline__ void stg(double* base, uint32_t byte_off, double v)
+{
+    asm volatile("" : "+v"(byte_off));
+    *reinterpret_cast<double*>(reinterpret_cast<char*>(base) + byte_off) = v;
+}
+
+// Workgroups are handed to the eight XCDs (each with its own L2) round-robin by workgroup id.
+// Giving XCD x the x-th contiguous eighth of the Morton-ordered blocks keeps a block and the
+// neighbours whose data it reads on the same L2.
+constexpr int NXCD = 8;
+__device__ __forceinline__ int64_t block_of_workgroup(int64_t wg, int64_t nb)
+{
+    const int64_t per = (nb + NXCD - 1) / NXCD;      // blocks per XCD
+    const int64_t b = (wg % NXCD) * per + wg / NXCD;
+    return b;                                        // may be >= nb for the last XCD: caller checks
 }
 
 __device__ __forceinline__ void load_block_info(BlockInfo& bi, const DeviceTree& tr, int64_t b, int tid)
@@ -77,41 +111,59 @@ __device__ __forceinline__ void load_block_info(BlockInfo& bi, const DeviceTree&
 
 constexpr int PLAN = (PBLK + NTHREADS - 1) / NTHREADS;   // 6 tile entries per thread
 
-struct FillPlan { int src[PLAN]; int dst[PLAN]; };        // src < 0: nothing to copy
+// Entries with nothing to copy (beyond the tile, or interpolated later) read element 0 and write
+// to DUMMY, a padding slot of the tile that no stencil reads; the copy loop is branch-free.
+constexpr int DUMMY = NP * RS;   // first padding slot behind plane 0
+// src: byte offset in the source array, kept in LDS as src[m * NTHREADS + tid] (it is needed once
+// per variable and registers are scarce); dst: tile index, two 16-bit values per register
+struct FillPlan {
+    uint32_t* src;
+    uint32_t dstp[PLAN / 2];
+    __device__ __forceinline__ int dst(int m) const { return (dstp[m >> 1] >> (16 * (m & 1))) & 0xffff; }
+    __device__ __forceinline__ void set_dst(int m, int v) { dstp[m >> 1] = (m & 1) ? (dstp[m >> 1] | ((uint32_t)v << 16)) : (uint32_t)v; }
+};
+static_assert(PLAN % 2 == 0 && TILE < 65536, "tile indices are packed in pairs");
 
-// Source of every padded point this thread fills, as an offset into one variable's zipped array
-// (same-level copy or injection from a finer leaf).  Points whose source is coarser are left to
-// the interpolation passes.
+// Source of every padded point this thread fills, as a byte offset into one variable's zipped
+// array (same-level copy or injection from a finer leaf).  Points whose source is coarser are left
+// to the interpolation passes.
 __device__ __forceinline__ void make_plan_zipped(FillPlan& fp, const BlockInfo& bi, int tid)
 {
 #pragma unroll
     for (int m = 0; m < PLAN; ++m) {
         const int p = tid + m * NTHREADS;
-        fp.src[m] = -1; fp.dst[m] = 0;
-        if (p >= PBLK) continue;
-        const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
-        fp.dst[m] = tidx(kk, jj, ii);
-        const int rx = ii < PAD ? 0 : (ii < PAD + NPT ? 1 : 2);
-        const int ry = jj < PAD ? 0 : (jj < PAD + NPT ? 1 : 2);
-        const int rz = kk < PAD ? 0 : (kk < PAD + NPT ? 1 : 2);
-        const int32_t* e = &bi.gt[(rz * 9 + ry * 3 + rx) * 5];
-        const int kind = e[0];
-        if (kind == K_COARSER) continue;
-        // coordinates inside the neighbouring octant of the same level, 0..7
-        const int lx = ii - PAD + (1 - rx) * NPT, ly = jj - PAD + (1 - ry) * NPT, lz = kk - PAD + (1 - rz) * NPT;
-        if (kind == K_SAME) {
-            fp.src[m] = e[1] * BLK + (lz * NPT + ly) * NPT + lx;
-        } else {
-            // which child holds the point: forced by the direction on non-free axes
-            const int bx = rx == 1 ? (lx >> 2) : (rx == 0 ? 1 : 0);
-            const int by = ry == 1 ? (ly >> 2) : (ry == 0 ? 1 : 0);
-            const int bz = rz == 1 ? (lz >> 2) : (rz == 0 ? 1 : 0);
-            int q = 0, sh = 0;
-            if (rx == 1) { q |= bx << sh; ++sh; }
-            if (ry == 1) { q |= by << sh; ++sh; }
-            if (rz == 1) { q |= bz << sh; }
-            fp.src[m] = e[1 + q] * BLK + ((2 * lz - NPT * bz) * NPT + (2 * ly - NPT * by)) * NPT + (2 * lx - NPT * bx);
+        uint32_t src = 0;
+        int dst = DUMMY;
+        if (p < PBLK) {
+            const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
+            const int rx = ii < PAD ? 0 : (ii < PAD + NPT ? 1 : 2);
+            const int ry = jj < PAD ? 0 : (jj < PAD + NPT ? 1 : 2);
+            const int rz = kk < PAD ? 0 : (kk < PAD + NPT ? 1 : 2);
+            const int32_t* e = &bi.gt[(rz * 9 + ry * 3 + rx) * 5];
+            const int kind = e[0];
+            if (kind != K_COARSER) {
+                // coordinates inside the neighbouring octant of the same level, 0..7
+                const int lx = ii - PAD + (1 - rx) * NPT, ly = jj - PAD + (1 - ry) * NPT, lz = kk - PAD + (1 - rz) * NPT;
+                dst = tidx(kk, jj, ii);
+                uint32_t elem;
+                if (kind == K_SAME) {
+                    elem = (uint32_t)e[1] * BLK + (lz * NPT + ly) * NPT + lx;
+                } else {
+                    // which child holds the point: forced by the direction on non-free axes
+                    const int bx = rx == 1 ? (lx >> 2) : (rx == 0 ? 1 : 0);
+                    const int by = ry == 1 ? (ly >> 2) : (ry == 0 ? 1 : 0);
+                    const int bz = rz == 1 ? (lz >> 2) : (rz == 0 ? 1 : 0);
+                    int q = 0, sh = 0;
+                    if (rx == 1) { q |= bx << sh; ++sh; }
+                    if (ry == 1) { q |= by << sh; ++sh; }
+                    if (rz == 1) { q |= bz << sh; }
+                    elem = (uint32_t)e[1 + q] * BLK + ((2 * lz - NPT * bz) * NPT + (2 * ly - NPT * by)) * NPT + (2 * lx - NPT * bx);
+                }
+                src = elem * 8u;
+            }
         }
+        fp.src[m * NTHREADS + tid] = src;
+        fp.set_dst(m, dst);
     }
 }
 
@@ -122,8 +174,8 @@ __device__ __forceinline__ void make_plan_padded(FillPlan& fp, int tid)
         const int p = tid + m * NTHREADS;
         const bool ok = p < PBLK;
         const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
-        fp.src[m] = ok ? p : -1;
-        fp.dst[m] = ok ? tidx(kk, jj, ii) : 0;
+        fp.src[m * NTHREADS + tid] = ok ? p * 8u : 0u;
+        fp.set_dst(m, ok ? tidx(kk, jj, ii) : DUMMY);
     }
 }
 
@@ -145,57 +197,71 @@ __device__ __forceinline__ double interp_line(const double* v, int st, int f, co
     return acc;
 }
 
-// Fill the tile of one variable.  `base` is that variable's zipped array (ZIN) or this block's
-// padded data.  All threads call this; it ends with a barrier.  `scratch` is SCRATCH doubles.
-template <bool ZIN>
-__device__ __forceinline__ void fill_tile(double* tile, double* scratch, const BlockInfo& bi, const FillPlan& fp,
-                                          const double* __restrict__ base, int tid)
+// q / d for the few divisors that occur here (3, 8, 11, 14 and their pairwise products), q < 65536
+__device__ __forceinline__ uint32_t div_magic(uint32_t d) { return 0xffffffffu / d + 1u; }
+__device__ __forceinline__ int div_by(int q, uint32_t magic) { return (int)__umulhi((uint32_t)q, magic); }
+
+// Filling the tile of one variable is split in two so that the global loads of the next variable
+// can be in flight while the current one is being differentiated:
+//   prefetch(): issue the planned loads into registers;
+//   commit():   store them into a tile buffer, then (zipped input only) interpolate the boxes whose
+//               source leaf is coarser.  `base` is that variable's zipped array (ZIN) or this
+//               block's padded data.  All threads call both.  commit() does NOT end with a barrier.
+__device__ __forceinline__ void prefetch(double (&v)[PLAN], const FillPlan& fp, const double* __restrict__ base, int tid)
 {
-    double v[PLAN];
+    uint32_t off[PLAN];
 #pragma unroll
-    for (int m = 0; m < PLAN; ++m) if (fp.src[m] >= 0) v[m] = base[fp.src[m]];
+    for (int m = 0; m < PLAN; ++m) off[m] = fp.src[m * NTHREADS + tid];
 #pragma unroll
-    for (int m = 0; m < PLAN; ++m) if (fp.src[m] >= 0) tile[fp.dst[m]] = v[m];
-    if (ZIN) {
+    for (int m = 0; m < PLAN; ++m) v[m] = (OCTFD_SKIP & 2) ? 1.0 : ldg(base, off[m]);
+}
+
+template <bool ZIN>
+__device__ __forceinline__ void commit(double* tile, double* scratch, const BlockInfo& bi, const FillPlan& fp,
+                                       const double (&v)[PLAN], const double* __restrict__ base, int tid)
+{
+#pragma unroll
+    for (int m = 0; m < PLAN; ++m) tile[fp.dst(m)] = v[m];
+    if (ZIN && bi.cs[0] >= 0) {
         // every coarser source leaf covers a box of the padded block; interpolate box by box,
-        // x then y then z.  Control flow is uniform over the workgroup.
-        double* C = scratch;             // the coarse leaf, 8^3
-        double* T1 = C + BLK;            // after the x pass  [cz][cy][tx], row stride NP
+        // x then y then z.  Control flow is uniform over the workgroup.  The staging arrays share
+        // LDS with the mixed-derivative arrays, which other wavefronts may still be reading.
+        double* T1 = scratch;            // after the x pass  [cz][cy][tx], row stride NP
         double* T2 = T1 + T1N;           // after the y pass  [cz][ty][tx]
+        double* C = T2;                  // the coarse leaf, 8^3: dead once the x pass is done
         for (int sidx = 0; sidx < 8; ++sidx) {
             const int32_t id = bi.cs[2 * sidx];
             if (id < 0) break;
+            __syncthreads();             // everybody is done with the staging arrays (C overlays T2)
             const int pk = bi.cs[2 * sidx + 1];
             const int rxl = pk & 3, rxh = (pk >> 2) & 3, ryl = (pk >> 4) & 3, ryh = (pk >> 6) & 3, rzl = (pk >> 8) & 3, rzh = (pk >> 10) & 3;
             const int sx = rxl == 0 ? 0 : (rxl == 1 ? PAD : PAD + NPT), ex = rxh == 0 ? PAD : (rxh == 1 ? PAD + NPT : NP);
             const int sy = ryl == 0 ? 0 : (ryl == 1 ? PAD : PAD + NPT), ey = ryh == 0 ? PAD : (ryh == 1 ? PAD + NPT : NP);
             const int sz = rzl == 0 ? 0 : (rzl == 1 ? PAD : PAD + NPT), ez = rzh == 0 ? PAD : (rzh == 1 ? PAD + NPT : NP);
             const int nx = ex - sx, ny = ey - sy, nz = ez - sz;
+            const uint32_t mx = div_magic(nx), mxy = div_magic(nx * ny);
             // fine coordinate of the box's first point inside the coarse leaf (aligned to 16 points)
             const int fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
             const int fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
             const int fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
-            C[tid] = base[(int64_t)id * BLK + tid];
+            C[tid] = ldg(base, ((uint32_t)id * BLK + tid) * 8u);
             __syncthreads();
             for (int q = tid; q < 64 * nx; q += NTHREADS) {              // x pass
-                const int tx = q % nx, row = q / nx;                     // row = cz*8 + cy
+                const int row = div_by(q, mx), tx = q - row * nx;        // row = cz*8 + cy
                 T1[row * NP + tx] = interp_line(&C[row * NPT], 1, fx0 + tx, bi.lag);
             }
             __syncthreads();
             for (int q = tid; q < NPT * ny * nx; q += NTHREADS) {        // y pass
-                const int tx = q % nx, ty = (q / nx) % ny, cz = q / (nx * ny);
+                const int cz = div_by(q, mxy), r = q - cz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
                 T2[(cz * NP + ty) * NP + tx] = interp_line(&T1[cz * NPT * NP + tx], NP, fy0 + ty, bi.lag);
             }
             __syncthreads();
             for (int q = tid; q < nz * ny * nx; q += NTHREADS) {         // z pass, into the tile
-                const int tx = q % nx, ty = (q / nx) % ny, tz = q / (nx * ny);
+                const int tz = div_by(q, mxy), r = q - tz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
                 tile[tidx(sz + tz, sy + ty, sx + tx)] = interp_line(&T2[ty * NP + tx], NP * NP, fz0 + tz, bi.lag);
             }
-            // the next source may overwrite C at once (last read two barriers ago); T1 and T2 are
-            // rewritten only after further barriers
         }
     }
-    __syncthreads();
 }
 
 // ---------------------------------------------------------------- stencils on the LDS tile
@@ -244,212 +310,318 @@ __device__ __forceinline__ AxisOps axis_ops(const double* t, int c, int st, doub
 
 struct PointOps { double u0, dx, dy, dz, lap, ko, dxx, dyy, dzz; };
 
+// The three axes are evaluated one after the other (the scheduling fences keep the compiler from
+// fetching all 19 taps up front): fewer values are live at once, which is what lets two workgroups
+// share a compute unit.
 template <bool WITH_D2>
 __device__ __forceinline__ PointOps point_ops(const double* t, int c, double sigma, double ih, double ih2)
 {
     PointOps r;
     r.u0 = t[c];
     const AxisOps x = axis_ops<WITH_D2>(t, c, 1, r.u0, ih, ih2);
+    r.dx = x.d1; r.dxx = x.d2;
+    __builtin_amdgcn_sched_barrier(0);
     const AxisOps y = axis_ops<WITH_D2>(t, c, RS, r.u0, ih, ih2);
+    r.dy = y.d1; r.dyy = y.d2;
+    const double kxy = x.ko + y.ko, lxy = x.d2 + y.d2;
+    __builtin_amdgcn_sched_barrier(0);
     const AxisOps z = axis_ops<WITH_D2>(t, c, PS, r.u0, ih, ih2);
-    r.dx = x.d1; r.dy = y.d1; r.dz = z.d1;
-    r.dxx = x.d2; r.dyy = y.d2; r.dzz = z.d2;
-    r.lap = (x.d2 + y.d2) + z.d2;
-    r.ko = sigma * (((x.ko + y.ko) + z.ko) * (ih * 0.015625));
+    r.dz = z.d1; r.dzz = z.d2;
+    r.lap = lxy + z.d2;
+    r.ko = sigma * ((kxy + z.ko) * (ih * 0.015625));
+    __builtin_amdgcn_sched_barrier(0);
     return r;
 }
 
 struct Mixed { double dxy, dxz, dyz; };
 
-// Mixed derivatives of the variable in `tile` at this thread's point (i, j, k):
+// Mixed derivatives of the variable in `tile` at this thread's point:
 //   dxy = D1_x(D1_y u), dxz = D1_x(D1_z u), dyz = D1_y(D1_z u).
-// wy [8][8][14] and wz [8][14][14] receive D1_y u and D1_z u; dy, dz are this thread's own values.
-// Contains one barrier; the arrays may be reused after the next barrier.
-__device__ __forceinline__ Mixed mixed_derivs(const double* tile, double* wy, double* wz, int tid, int i, int j, int k,
-                                              double dy, double dz, double ih)
+// wy [8][8][14] and wz [8][14][14] hold D1_y u and D1_z u; every thread has already stored the
+// values of its own point (indices owny, ownz).  The 3-deep ghost positions are whole-wavefront
+// tasks: wavefronts 0..5 each take one ghost x index (64 (j,k) columns, both operators),
+// wavefronts 2..7 each take one ghost y index.  Contains one barrier; the arrays may be reused
+// after the next barrier.
+__device__ __forceinline__ Mixed mixed_derivs(const double* tile, double* wy, double* wz, int tid, int owny, int ownz, double ih)
 {
-    wy[k * YPS + j * RS + (i + PAD)] = dy;
-    wz[k * PS + (j + PAD) * RS + (i + PAD)] = dz;
-    // ghost positions: 3 sets of 6 x 64 entries
-    //   set 0: D1_y u at (ii ghost, j, k)      -> wy
-    //   set 1: D1_z u at (ii ghost, j, k)      -> wz
-    //   set 2: D1_z u at (i, jj ghost, k)      -> wz
-#pragma unroll
-    for (int m = 0; m < 3; ++m) {
-        const int q = tid + m * NTHREADS;
-        if (q >= 3 * 384) break;
-        const int set = q / 384, r = q % 384;
-        if (set == 2) {
-            const int g = r >> 6, kk = (r >> 3) & 7, ii = r & 7;
-            const int jj = g < 3 ? g : g + NPT;
-            wz[kk * PS + jj * RS + (ii + PAD)] = d1_at(tile, tidx(kk + PAD, jj, ii + PAD), PS, ih);
-        } else {
-            const int g = r % 6, jk = r / 6, jj = jk & 7, kk = jk >> 3;
-            const int ii = g < 3 ? g : g + NPT;
-            const int c = tidx(kk + PAD, jj + PAD, ii);
-            if (set == 0) wy[kk * YPS + jj * RS + ii] = d1_at(tile, c, RS, ih);
-            else wz[kk * PS + (jj + PAD) * RS + ii] = d1_at(tile, c, PS, ih);
-        }
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int la = tid & 7, lb = (tid >> 3) & 7;       // lane coordinates inside the task
+    if (w < 6) {                                        // ghost x index ii, lanes = (j, k)
+        const int ii = w < 3 ? w : w + NPT;
+        const int ct = tidx(lb + PAD, la + PAD, ii);
+        wy[lb * YPS + la * RS + ii] = d1_at(tile, ct, RS, ih);
+        wz[lb * PS + (la + PAD) * RS + ii] = d1_at(tile, ct, PS, ih);
+    }
+    if (w >= 2) {                                       // ghost y index jj, lanes = (i, k)
+        const int g = w - 2, jj = g < 3 ? g : g + NPT;
+        const int ct = tidx(lb + PAD, jj, la + PAD);
+        wz[lb * PS + jj * RS + (la + PAD)] = d1_at(tile, ct, PS, ih);
     }
     __syncthreads();
     Mixed r;
-    r.dxy = d1_at(wy, k * YPS + j * RS + (i + PAD), 1, ih);
-    const int cz = k * PS + (j + PAD) * RS + (i + PAD);
-    r.dxz = d1_at(wz, cz, 1, ih);
-    r.dyz = d1_at(wz, cz, RS, ih);
+    r.dxy = d1_at(wy, owny, 1, ih);
+    __builtin_amdgcn_sched_barrier(0);
+    r.dxz = d1_at(wz, ownz, 1, ih);
+    __builtin_amdgcn_sched_barrier(0);
+    r.dyz = d1_at(wz, ownz, RS, ih);
     return r;
 }
 
 // ---------------------------------------------------------------- output
 
+// The Runge-Kutta epilogues read the accumulator and the state at the thread's own point.  Those
+// loads are issued at the start of a variable's pass (epi_prefetch) and consumed at its end (emit),
+// so their latency hides behind the stencil work.
+// o8 = byte offset of this thread's point inside one variable's zipped array, p8 = inside one
+// padded block; w selects the variable and b the block (both uniform).
+struct EpiOperands { double acc, u; };
+
 template <int EPI>
-__device__ __forceinline__ void emit(const RhsArgs& a, int64_t nb, int w, int64_t b, int pz, int cpad, double k)
+__device__ __forceinline__ EpiOperands epi_prefetch(const RhsArgs& a, int64_t nb, int w, uint32_t o8)
+{
+    EpiOperands e{0.0, 0.0};
+    const int64_t f = (int64_t)w * nb * BLK;
+    if (EPI == kRkFirst || EPI == kRkMiddle || EPI == kRkLast) e.u = ldg(a.u + f, o8);
+    if (EPI == kRkMiddle || EPI == kRkLast) e.acc = ldg(a.acc + f, o8);
+    return e;
+}
+
+template <int EPI>
+__device__ __forceinline__ void emit(const RhsArgs& a, int64_t nb, int w, int64_t b, uint32_t o8, uint32_t p8, double k,
+                                     const EpiOperands& e)
 {
     if (EPI == kOutPadded) {
-        a.out[((int64_t)w * nb + b) * PBLK + cpad] = k;
+        stg(a.out + ((int64_t)w * nb + b) * PBLK, p8, k);
         return;
     }
-    const int64_t o = ((int64_t)w * nb + b) * BLK + pz;
+    const int64_t f = (int64_t)w * nb * BLK;
+    if ((OCTFD_SKIP & 8) && k != 12345.678) return;
     if (EPI == kOutZipped) {
-        a.out[o] = k;
+        stg(a.out + f, o8, k);
     } else if (EPI == kRkFirst) {
-        a.acc[o] = k;
-        a.out[o] = fma(a.c, k, a.u[o]);
+        stg(a.acc + f, o8, k);
+        stg(a.out + f, o8, fma(a.c, k, e.u));
     } else if (EPI == kRkMiddle) {
-        a.acc[o] = a.acc[o] + 2.0 * k;
-        a.out[o] = fma(a.c, k, a.u[o]);
+        stg(a.acc + f, o8, e.acc + 2.0 * k);
+        stg(a.out + f, o8, fma(a.c, k, e.u));
     } else {
-        a.u[o] = fma(a.c, a.acc[o] + k, a.u[o]);
+        stg(a.u + f, o8, fma(a.c, e.acc + k, e.u));
     }
 }
 
 // ---------------------------------------------------------------- right-hand-side kernel
 
-struct Pending { double part, ko, t4, dx, dy, dz; };   // a SYN24 output waiting for the next field's gradient
+// One SYN24 variable at this thread's point, fused axis by axis so that few values are live at any
+// time (the scheduling fences keep the compiler from fetching every tap up front).  (nx, ny, nz)
+// holds the gradient of the successor variable on entry and this variable's own gradient on exit.
+//   t1 = beta . grad u,  t3q = grad u . grad u_next (before the factor 1/4),  ko = dissipation,
+//   diag = Gxx Dxx + Gyy Dyy + Gzz Dzz (WITH_D2 only).
+// WITH_D2 also publishes D1_y u and D1_z u of the own point for mixed_derivs().
+struct Syn24Part { double t1, t3q, ko, diag; };
 
-__device__ __forceinline__ double syn24_finish(const Pending& p, double dxn, double dyn, double dzn)
+template <bool WITH_D2>
+__device__ __forceinline__ Syn24Part syn24_axes(const double* t, int c, double* wy, double* wz, int owny, int ownz,
+                                                double& nx, double& ny, double& nz, double bx, double by, double bz,
+                                                double Gxx, double Gyy, double Gzz, double sigma, double ih, double ih2)
 {
-    double t3 = p.dx * dxn;
-    t3 = fma(p.dy, dyn, t3);
-    t3 = fma(p.dz, dzn, t3);
-    t3 = 0.25 * t3;
-    return ((p.part + t3) - p.t4) + p.ko;
+    Syn24Part r;
+    const double u0 = t[c];
+    r.diag = 0.0;
+    if (OCTFD_SKIP & 4) { r.t1 = u0; r.t3q = nx; r.ko = ny; nx = nz + u0; return r; }
+    const AxisOps x = axis_ops<WITH_D2>(t, c, 1, u0, ih, ih2);
+    r.t1 = bx * x.d1;
+    r.t3q = x.d1 * nx;
+    nx = x.d1;
+    if (WITH_D2) r.diag = Gxx * x.d2;
+    double ksum = x.ko;
+    __builtin_amdgcn_sched_barrier(0);
+    const AxisOps y = axis_ops<WITH_D2>(t, c, RS, u0, ih, ih2);
+    r.t1 = fma(by, y.d1, r.t1);
+    r.t3q = fma(y.d1, ny, r.t3q);
+    ny = y.d1;
+    if (WITH_D2) { r.diag = fma(Gyy, y.d2, r.diag); wy[owny] = y.d1; }
+    ksum = ksum + y.ko;
+    __builtin_amdgcn_sched_barrier(0);
+    const AxisOps z = axis_ops<WITH_D2>(t, c, PS, u0, ih, ih2);
+    r.t1 = fma(bz, z.d1, r.t1);
+    r.t3q = fma(z.d1, nz, r.t3q);
+    nz = z.d1;
+    if (WITH_D2) { r.diag = fma(Gzz, z.d2, r.diag); wz[ownz] = z.d1; }
+    r.ko = sigma * ((ksum + z.ko) * (ih * 0.015625));
+    __builtin_amdgcn_sched_barrier(0);
+    return r;
+}
+
+__device__ __forceinline__ double syn24_combine(const Syn24Part& p, int f, double lap, double halpha, double unext)
+{
+    const double kappa = __longlong_as_double((long long)(1023 - (f & 3)) << 52);   // 2^-(f mod 4)
+    const double t2 = kappa * lap;
+    const double t3 = 0.25 * p.t3q;
+    const double t4 = halpha * unext;
+    return (((p.t1 + t2) + t3) - t4) + p.ko;
+}
+
+// position t = 0..26 of the SYN24 variable stream -> variable.  Three gradient-only passes over
+// 10, 20, 0, then rounds (s, s+10[, s+20]) for s = 9 .. 0 (the third member exists for s < 4).
+__device__ __forceinline__ void syn24_stream(int t, int& field, int& s, int& sub)
+{
+    if (t < 3) { s = -1; sub = t; field = t == 0 ? 10 : (t == 1 ? 20 : 0); return; }
+    const int u = t - 3;
+    if (u < 12) { s = 9 - (u >> 1); sub = u & 1; }
+    else { const int v = u - 12, r = (v * 11) >> 5; s = 3 - r; sub = v - 3 * r; }
+    field = s + 10 * sub;
 }
 
 template <int KIND, bool ZIN, int EPI>
-__global__ __launch_bounds__(NTHREADS) void k_rhs(DeviceTree tr, RhsArgs a)
+__global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTree tr, RhsArgs a)
 {
-    __shared__ double tile[TILE];
+    constexpr int NBUF = KIND == OT_RHS_SYN24 ? 2 : 1;
+    __shared__ double tiles[NBUF * TILE];
     __shared__ double scratch[(ZIN || KIND == OT_RHS_SYN24) ? SCRATCH : 1];
     __shared__ BlockInfo bi;
+    __shared__ uint32_t plan_src[PLAN * NTHREADS];
 
     const int tid = threadIdx.x;
-    const int64_t b = blockIdx.x, nb = tr.nb;
+    const int64_t nb = tr.nb;
+    const int64_t b = block_of_workgroup(blockIdx.x, nb);
+    if (b >= nb) return;                             // uniform over the workgroup
     load_block_info(bi, tr, b, tid);
     __syncthreads();
 
     int i, j, k;
     point_of(tid, i, j, k);
     const int c = tidx(k + PAD, j + PAD, i + PAD);
-    const int pz = (k * NPT + j) * NPT + i;                          // offset inside a zipped block
-    const int cpad = ((k + PAD) * NP + (j + PAD)) * NP + (i + PAD);  // offset inside a padded block
+    // byte offsets of this thread's point inside one variable's zipped array / inside a padded block
+    const uint32_t o8 = ((uint32_t)b * BLK + (k * NPT + j) * NPT + i) * 8u;
+    const uint32_t p8 = (((k + PAD) * NP + (j + PAD)) * NP + (i + PAD)) * 8u;
     const double ih = (double)(NPT << bi.level), ih2 = ih * ih;
     const double sigma = a.sigma;
 
     FillPlan fp;
+    fp.src = plan_src;
     if (ZIN) make_plan_zipped(fp, bi, tid);
     else make_plan_padded(fp, tid);
+    double pv[PLAN];
 
-    auto stage = [&](int v) {   // bring variable v into the tile (barrier before and after)
+    auto var_base = [&](int v) -> const double* {
+        return ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK;
+    };
+    auto stage = [&](int v) {   // bring variable v into tile buffer 0 (barrier before and after)
         __syncthreads();
-        fill_tile<ZIN>(tile, scratch, bi, fp, ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK, tid);
+        prefetch(pv, fp, var_base(v), tid);
+        commit<ZIN>(tiles, scratch, bi, fp, pv, var_base(v), tid);
+        __syncthreads();
     };
     auto centre = [&](int v) -> double {   // this thread's own value of variable v
-        return ZIN ? a.in[((int64_t)v * nb + b) * BLK + pz] : a.in[((int64_t)v * nb + b) * PBLK + cpad];
+        return ZIN ? ldg(a.in + (int64_t)v * nb * BLK, o8) : ldg(a.in + ((int64_t)v * nb + b) * PBLK, p8);
     };
 
     if (KIND == OT_RHS_DERIVS) {
         stage(0);
-        const PointOps p = point_ops<true>(tile, c, 0.0, ih, ih2);
-        emit<EPI>(a, nb, 0, b, pz, cpad, p.dx);
-        emit<EPI>(a, nb, 1, b, pz, cpad, p.dy);
-        emit<EPI>(a, nb, 2, b, pz, cpad, p.dz);
-        emit<EPI>(a, nb, 3, b, pz, cpad, p.lap);
+        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
+        const EpiOperands e2 = epi_prefetch<EPI>(a, nb, 2, o8), e3 = epi_prefetch<EPI>(a, nb, 3, o8);
+        const PointOps p = point_ops<true>(tiles, c, 0.0, ih, ih2);
+        emit<EPI>(a, nb, 0, b, o8, p8, p.dx, e0);
+        emit<EPI>(a, nb, 1, b, o8, p8, p.dy, e1);
+        emit<EPI>(a, nb, 2, b, o8, p8, p.dz, e2);
+        emit<EPI>(a, nb, 3, b, o8, p8, p.lap, e3);
     } else if (KIND == OT_RHS_WAVE) {
+        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
         stage(0);
-        const PointOps pu = point_ops<true>(tile, c, sigma, ih, ih2);
+        const PointOps pu = point_ops<true>(tiles, c, sigma, ih, ih2);
         stage(1);
-        const PointOps pp = point_ops<false>(tile, c, sigma, ih, ih2);
-        emit<EPI>(a, nb, 0, b, pz, cpad, pp.u0 + pu.ko);
-        emit<EPI>(a, nb, 1, b, pz, cpad, pu.lap + pp.ko);
+        const PointOps pp = point_ops<false>(tiles, c, sigma, ih, ih2);
+        emit<EPI>(a, nb, 0, b, o8, p8, pp.u0 + pu.ko, e0);
+        emit<EPI>(a, nb, 1, b, o8, p8, pu.lap + pp.ko, e1);
     } else if (KIND == OT_RHS_BURGERS) {
         stage(0);
-        const PointOps p = point_ops<false>(tile, c, sigma, ih, ih2);
+        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8);
+        const PointOps p = point_ops<false>(tiles, c, sigma, ih, ih2);
         const double flux = p.u0 * p.dx;
-        emit<EPI>(a, nb, 0, b, pz, cpad, p.ko - flux);
+        emit<EPI>(a, nb, 0, b, o8, p8, p.ko - flux, e0);
     } else {
-        // SYN24.  Fields are streamed in the order s, s+10, s+20 for s = 0..9 so that the
-        // second-derivative combination Lap_s is consumed at once by the (up to) three outputs
-        // that use it; each output waits in a Pending slot for the gradient of the next field.
+        // SYN24.  Output a needs the gradient of variable a+1 (cyclically) and Lap_{a mod 10}.
+        // Variables are streamed in rounds (s, s+10, s+20) for s = 9 .. 0: Lap_s is consumed at once
+        // by the (up to) three outputs that use it, and every output finds the gradient of its
+        // successor left behind by the previous round.  The three gradients that close the cycle
+        // (variables 10, 20 and 0) come from three gradient-only passes at the start.  The tile is
+        // double-buffered: while variable t is differentiated out of one buffer, the loads of
+        // variable t+1 are in flight and are committed to the other buffer afterwards, so that
+        // one barrier per variable suffices (plus the one inside mixed_derivs).
         double* wz = scratch;
         double* wy = scratch + WZ;
-        const double alpha = centre(0), bx = centre(1), by = centre(2), bz = centre(3);
+        const double halpha = 0.5 * centre(0), bx = centre(1), by = centre(2), bz = centre(3);
         const double Gxx = 1.0 - 0.125 * centre(4), Gxy = -(0.125 * centre(5)), Gxz = -(0.125 * centre(6));
         const double Gyy = 1.0 - 0.125 * centre(7), Gyz = -(0.125 * centre(8)), Gzz = 1.0 - 0.125 * centre(9);
-        const double halpha = 0.5 * alpha;
-        Pending P0, P1, P2;
-        double g0x = 0, g0y = 0, g0z = 0, g10x = 0, g10y = 0, g10z = 0, g20x = 0, g20y = 0, g20z = 0;
+        double n0x = 0, n0y = 0, n0z = 0, n1x = 0, n1y = 0, n1z = 0, n2x = 0, n2y = 0, n2z = 0;
+        double lap = 0;
+        constexpr int NSTREAM = 27;
+        const int ownz = k * PS + (j + PAD) * RS + (i + PAD), owny = k * YPS + j * RS + (i + PAD);
 
-        auto open_slot = [&](Pending& P, int f, const PointOps& p, double lap, double unext) {
-            double t1 = bx * p.dx;
-            t1 = fma(by, p.dy, t1);
-            t1 = fma(bz, p.dz, t1);
-            const double kappa = __longlong_as_double((long long)(1023 - (f & 3)) << 52);   // 2^-(f mod 4)
-            P.part = t1 + kappa * lap;
-            P.ko = p.ko;
-            P.t4 = halpha * unext;
-            P.dx = p.dx; P.dy = p.dy; P.dz = p.dz;
-        };
+        // Memory latency is about as long as one variable's pass, so everything that comes from
+        // global memory is requested two passes ahead of its use: tile data for variable t+2 is
+        // loaded into one of two register sets at the top of pass t and committed to LDS at the end
+        // of pass t+1; the pointwise operands of pass t+1 (RK accumulator and state, the
+        // u_{a+11} factor) are requested at the top of pass t.  The register sets alternate, hence
+        // the pass body is instantiated twice.
+        struct Look { double unext; EpiOperands eo; };
+        double pv1[PLAN];
+        Look lk0{0.0, {0.0, 0.0}}, lk1{0.0, {0.0, 0.0}};
 
-#pragma unroll 1
-        for (int s = 0; s < 10; ++s) {
-            double lap;
-            {
-                const double unext = centre((s + 11) % 24);
-                stage(s);
-                const PointOps p = point_ops<true>(tile, c, sigma, ih, ih2);
-                const Mixed mx = mixed_derivs(tile, wy, wz, tid, i, j, k, p.dy, p.dz, ih);
-                double diag = Gxx * p.dxx;
-                diag = fma(Gyy, p.dyy, diag);
-                diag = fma(Gzz, p.dzz, diag);
+        auto pass = [&](int t, double (&p_issue)[PLAN], double (&p_commit)[PLAN], Look& l_issue, const Look& l_use) {
+            const double* T = tiles + (t & 1) * TILE;
+            int f, s, sub, f1 = 0, s1 = -1, sub1 = 0, f2 = 0, s2, sub2;
+            syn24_stream(t, f, s, sub);
+            if (t + 2 < NSTREAM) {
+                syn24_stream(t + 2, f2, s2, sub2);
+                prefetch(p_issue, fp, var_base(f2), tid);
+            }
+            if (t + 1 < NSTREAM) {
+                syn24_stream(t + 1, f1, s1, sub1);
+                if (s1 >= 0) {
+                    l_issue.unext = centre((f1 + 11) % 24);
+                    l_issue.eo = epi_prefetch<EPI>(a, nb, f1, o8);
+                }
+            }
+            if (s < 0) {                      // gradient-only pass
+                const double gx = d1_at(T, c, 1, ih), gy = d1_at(T, c, RS, ih), gz = d1_at(T, c, PS, ih);
+                if (sub == 0) { n0x = gx; n0y = gy; n0z = gz; }
+                else if (sub == 1) { n1x = gx; n1y = gy; n1z = gz; }
+                else { n2x = gx; n2y = gy; n2z = gz; }
+            } else if (sub == 0) {
+                const Syn24Part p = syn24_axes<true>(T, c, wy, wz, owny, ownz, n0x, n0y, n0z, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
+                Mixed mx;
+                if (OCTFD_SKIP & 1) { mx.dxy = p.t1; mx.dxz = p.t3q; mx.dyz = p.ko; }
+                else mx = mixed_derivs(T, wy, wz, tid, owny, ownz, ih);
                 double off = Gxy * mx.dxy;
                 off = fma(Gxz, mx.dxz, off);
                 off = fma(Gyz, mx.dyz, off);
-                lap = fma(2.0, off, diag);
-                if (s > 0) emit<EPI>(a, nb, s - 1, b, pz, cpad, syn24_finish(P0, p.dx, p.dy, p.dz));
-                else { g0x = p.dx; g0y = p.dy; g0z = p.dz; }
-                open_slot(P0, s, p, lap, unext);
+                lap = fma(2.0, off, p.diag);
+                emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l_use.unext), l_use.eo);
+            } else {
+                Syn24Part p;
+                if (sub == 1) p = syn24_axes<false>(T, c, wy, wz, owny, ownz, n1x, n1y, n1z, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
+                else p = syn24_axes<false>(T, c, wy, wz, owny, ownz, n2x, n2y, n2z, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
+                emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l_use.unext), l_use.eo);
             }
-            {
-                const double unext = centre((s + 21) % 24);
-                stage(s + 10);
-                const PointOps p = point_ops<false>(tile, c, sigma, ih, ih2);
-                if (s > 0) emit<EPI>(a, nb, s + 9, b, pz, cpad, syn24_finish(P1, p.dx, p.dy, p.dz));
-                else { g10x = p.dx; g10y = p.dy; g10z = p.dz; }
-                open_slot(P1, s + 10, p, lap, unext);
-            }
-            if (s < 4) {
-                const double unext = centre((s + 31) % 24);
-                stage(s + 20);
-                const PointOps p = point_ops<false>(tile, c, sigma, ih, ih2);
-                if (s > 0) emit<EPI>(a, nb, s + 19, b, pz, cpad, syn24_finish(P2, p.dx, p.dy, p.dz));
-                else { g20x = p.dx; g20y = p.dy; g20z = p.dz; }
-                open_slot(P2, s + 20, p, lap, unext);
-            }
+            if (t + 1 < NSTREAM) commit<ZIN>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, p_commit, var_base(f1), tid);
+            __syncthreads();
+        };
+
+        {
+            int f, s, sub;
+            syn24_stream(0, f, s, sub);
+            prefetch(pv, fp, var_base(f), tid);
+            commit<ZIN>(tiles, scratch, bi, fp, pv, var_base(f), tid);
+            syn24_stream(1, f, s, sub);
+            prefetch(pv1, fp, var_base(f), tid);
+            __syncthreads();
         }
-        emit<EPI>(a, nb, 9, b, pz, cpad, syn24_finish(P0, g10x, g10y, g10z));
-        emit<EPI>(a, nb, 19, b, pz, cpad, syn24_finish(P1, g20x, g20y, g20z));
-        emit<EPI>(a, nb, 23, b, pz, cpad, syn24_finish(P2, g0x, g0y, g0z));
+#pragma unroll 1
+        for (int t = 0; t < NSTREAM; t += 2) {
+            pass(t, pv, pv1, lk1, lk0);
+            if (t + 1 < NSTREAM) pass(t + 1, pv1, pv, lk0, lk1);
+        }
     }
 }
 
@@ -460,18 +632,24 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, const double*
     __shared__ double tile[TILE];
     __shared__ double scratch[SCRATCH];
     __shared__ BlockInfo bi;
+    __shared__ uint32_t plan_src[PLAN * NTHREADS];
     const int tid = threadIdx.x;
     const int64_t b = blockIdx.x, v = blockIdx.y, nb = tr.nb;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
     FillPlan fp;
+    fp.src = plan_src;
     make_plan_zipped(fp, bi, tid);
-    fill_tile<true>(tile, scratch, bi, fp, zipped + v * nb * BLK, tid);
+    double pv[PLAN];
+    prefetch(pv, fp, zipped + v * nb * BLK, tid);
+    commit<true>(tile, scratch, bi, fp, pv, zipped + v * nb * BLK, tid);
+    __syncthreads();
     double* out = padded + (v * nb + b) * PBLK;
 #pragma unroll
     for (int m = 0; m < PLAN; ++m) {
         const int p = tid + m * NTHREADS;
-        if (p < PBLK) out[p] = tile[fp.dst[m]];
+        const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
+        if (p < PBLK) out[p] = tile[tidx(kk, jj, ii)];
     }
 }
 
@@ -487,7 +665,8 @@ __global__ __launch_bounds__(NTHREADS) void k_zip(int64_t nblocks, const double*
 template <int KIND, bool ZIN, int EPI>
 hipError_t launch_one(const DeviceTree& t, const RhsArgs& a, hipStream_t s)
 {
-    hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI>), dim3((unsigned)t.nb), dim3(NTHREADS), 0, s, t, a);
+    const int64_t per = (t.nb + NXCD - 1) / NXCD;
+    hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI>), dim3((unsigned)(per * NXCD)), dim3(NTHREADS), 0, s, t, a);
     return hipGetLastError();
 }
 

@@ -182,7 +182,7 @@ int rhs_eval(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, const
 {
     if (!tree || !kind_ok(kind) || !params || !padded_dev || !rhs_padded_dev) return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
-    RhsArgs a{padded_dev, rhs_padded_dev, nullptr, nullptr, 0.0, params->ko_sigma};
+    RhsArgs a{padded_dev, rhs_padded_dev, nullptr, nullptr, rhs_padded_dev, 0.0, params->ko_sigma};
     hipError_t e = launch_rhs(dev_view(tree), kind, false, kOutPadded, a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
@@ -192,7 +192,7 @@ int rhs_eval_zipped(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params
 {
     if (!tree || !kind_ok(kind) || !params || !zipped_dev || !rhs_zipped_dev) return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
-    RhsArgs a{zipped_dev, rhs_zipped_dev, nullptr, nullptr, 0.0, params->ko_sigma};
+    RhsArgs a{zipped_dev, rhs_zipped_dev, nullptr, nullptr, rhs_zipped_dev, 0.0, params->ko_sigma};
     hipError_t e = launch_rhs(dev_view(tree), kind, true, kOutZipped, a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
@@ -225,10 +225,10 @@ int rk_step(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double
     // stage vectors ping-pong between sa and sb: a stage reads ghosts of the vector it was given
     // while writing the next one, so the two must be different arrays
     const RhsArgs st[4] = {
-        {u, sa, acc, u, 0.5 * dt, sg},    // k1 = F(u):   acc = k1,        sa = u + dt/2 k1
-        {sa, sb, acc, u, 0.5 * dt, sg},   // k2 = F(sa):  acc += 2 k2,     sb = u + dt/2 k2
-        {sb, sa, acc, u, dt, sg},         // k3 = F(sb):  acc += 2 k3,     sa = u + dt k3
-        {sa, nullptr, acc, u, dt / 6.0, sg}};   // k4 = F(sa):  u += dt/6 (acc + k4)
+        {u, sa, acc, u, sa, 0.5 * dt, sg},    // k1 = F(u):   acc = k1,        sa = u + dt/2 k1
+        {sa, sb, acc, u, sb, 0.5 * dt, sg},   // k2 = F(sa):  acc += 2 k2,     sb = u + dt/2 k2
+        {sb, sa, acc, u, sa, dt, sg},         // k3 = F(sb):  acc += 2 k3,     sa = u + dt k3
+        {sa, nullptr, acc, u, sb, dt / 6.0, sg}};   // k4 = F(sa):  u += dt/6 (acc + k4); sb is free scratch
     const Epilogue ep[4] = {kRkFirst, kRkMiddle, kRkMiddle, kRkLast};
     for (int i = 0; i < 4; ++i) {
         hipError_t e = launch_rhs(dv, kind, true, ep[i], st[i], s);

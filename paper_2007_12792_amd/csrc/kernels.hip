@@ -461,16 +461,12 @@ __device__ __forceinline__ double syn24_combine(const Syn24Part& p, int f, doubl
     return (((p.t1 + t2) + t3) - t4) + p.ko;
 }
 
-// position t = 0..26 of the SYN24 variable stream -> variable.  Three gradient-only passes over
-// 10, 20, 0, then rounds (s, s+10[, s+20]) for s = 9 .. 0 (the third member exists for s < 4).
-__device__ __forceinline__ void syn24_stream(int t, int& field, int& s, int& sub)
-{
-    if (t < 3) { s = -1; sub = t; field = t == 0 ? 10 : (t == 1 ? 20 : 0); return; }
-    const int u = t - 3;
-    if (u < 12) { s = 9 - (u >> 1); sub = u & 1; }
-    else { const int v = u - 12, r = (v * 11) >> 5; s = 3 - r; sub = v - 3 * r; }
-    field = s + 10 * sub;
-}
+// position t = 0..24 of the SYN24 variable stream -> variable.  Output a needs the gradient of
+// variable a+1 (cyclically), so the variables are visited in descending cyclic order starting at 9:
+// one gradient-only pass over variable 10, then 9, 8, ..., 0, 23, 22, ..., 10.  Every pass leaves
+// its own gradient behind for the next one.
+constexpr int NSTREAM = 25;
+__device__ __forceinline__ int syn24_stream(int t) { return t == 0 ? 10 : (t <= 10 ? 10 - t : 34 - t); }
 
 template <int KIND, bool ZIN, int EPI>
 __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTree tr, RhsArgs a)
@@ -485,8 +481,10 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
     const int64_t nb = tr.nb;
     const int64_t b = block_of_workgroup(blockIdx.x, nb);
     if (b >= nb) return;                             // uniform over the workgroup
+    if (OCTFD_SKIP & 16) { if (tid == 0) tiles[0] = 1.0; return; }   // timing experiment: launch cost only
     load_block_info(bi, tr, b, tid);
     __syncthreads();
+    if (OCTFD_SKIP & 32) { if (tid == 0) tiles[0] = bi.lag[3]; return; }   // timing experiment: + block info
 
     int i, j, k;
     point_of(tid, i, j, k);
@@ -502,6 +500,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
     if (ZIN) make_plan_zipped(fp, bi, tid);
     else make_plan_padded(fp, tid);
     double pv[PLAN];
+    if (OCTFD_SKIP & 64) { tiles[tid] = (double)(fp.dstp[0] + fp.dstp[1] + fp.dstp[2]); return; }   // timing experiment: + plan
 
     auto var_base = [&](int v) -> const double* {
         return ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK;
@@ -540,88 +539,89 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
         const double flux = p.u0 * p.dx;
         emit<EPI>(a, nb, 0, b, o8, p8, p.ko - flux, e0);
     } else {
-        // SYN24.  Output a needs the gradient of variable a+1 (cyclically) and Lap_{a mod 10}.
-        // Variables are streamed in rounds (s, s+10, s+20) for s = 9 .. 0: Lap_s is consumed at once
-        // by the (up to) three outputs that use it, and every output finds the gradient of its
-        // successor left behind by the previous round.  The three gradients that close the cycle
-        // (variables 10, 20 and 0) come from three gradient-only passes at the start.  The tile is
-        // double-buffered: while variable t is differentiated out of one buffer, the loads of
-        // variable t+1 are in flight and are committed to the other buffer afterwards, so that
-        // one barrier per variable suffices (plus the one inside mixed_derivs).
+        // SYN24.  The variables are streamed in descending cyclic order (see syn24_stream).  The
+        // first ten real passes (variables 9..0) evaluate the second-derivative combinations Lap_s;
+        // each thread parks them at its own point in variables 10+s of the `stash` array, from where
+        // the later passes (variables 23..10, which need Lap_{a mod 10}) read them back before those
+        // slots receive their final values.  Per-thread state thus shrinks to one gradient.
+        //
+        // The tile is double-buffered and global memory is requested ahead of its use: tile data
+        // of the next variable is loaded into registers at the top of a pass and committed to the
+        // other LDS buffer at its end (one barrier per pass, plus the one inside mixed_derivs); the
+        // pointwise operands of the next pass (RK accumulator and state, u_{a+11}, Lap) likewise.
         double* wz = scratch;
         double* wy = scratch + WZ;
         const double halpha = 0.5 * centre(0), bx = centre(1), by = centre(2), bz = centre(3);
         const double Gxx = 1.0 - 0.125 * centre(4), Gxy = -(0.125 * centre(5)), Gxz = -(0.125 * centre(6));
         const double Gyy = 1.0 - 0.125 * centre(7), Gyz = -(0.125 * centre(8)), Gzz = 1.0 - 0.125 * centre(9);
-        double n0x = 0, n0y = 0, n0z = 0, n1x = 0, n1y = 0, n1z = 0, n2x = 0, n2y = 0, n2z = 0;
-        double lap = 0;
-        constexpr int NSTREAM = 27;
+        double nx = 0, ny = 0, nz = 0;
         const int ownz = k * PS + (j + PAD) * RS + (i + PAD), owny = k * YPS + j * RS + (i + PAD);
+        struct Look { double unext, lap; EpiOperands eo; };
 
-        // Memory latency is about as long as one variable's pass, so everything that comes from
-        // global memory is requested two passes ahead of its use: tile data for variable t+2 is
-        // loaded into one of two register sets at the top of pass t and committed to LDS at the end
-        // of pass t+1; the pointwise operands of pass t+1 (RK accumulator and state, the
-        // u_{a+11} factor) are requested at the top of pass t.  The register sets alternate, hence
-        // the pass body is instantiated twice.
-        struct Look { double unext; EpiOperands eo; };
-        double pv1[PLAN];
-        Look lk0{0.0, {0.0, 0.0}}, lk1{0.0, {0.0, 0.0}};
+        auto stash_base = [&](int v) -> double* {   // where Lap_{v-10} is parked (v = 10..19)
+            return EPI == kOutPadded ? a.stash + ((int64_t)v * nb + b) * PBLK : a.stash + (int64_t)v * nb * BLK;
+        };
+        const uint32_t s8 = EPI == kOutPadded ? p8 : o8;
 
-        auto pass = [&](int t, double (&p_issue)[PLAN], double (&p_commit)[PLAN], Look& l_issue, const Look& l_use) {
-            const double* T = tiles + (t & 1) * TILE;
-            int f, s, sub, f1 = 0, s1 = -1, sub1 = 0, f2 = 0, s2, sub2;
-            syn24_stream(t, f, s, sub);
-            if (t + 2 < NSTREAM) {
-                syn24_stream(t + 2, f2, s2, sub2);
-                prefetch(p_issue, fp, var_base(f2), tid);
-            }
+        // top of pass t: request the tile data of pass t+1 and this pass's own pointwise operands
+        auto issue = [&](int t, int f, Look& l, int& f1) {
             if (t + 1 < NSTREAM) {
-                syn24_stream(t + 1, f1, s1, sub1);
-                if (s1 >= 0) {
-                    l_issue.unext = centre((f1 + 11) % 24);
-                    l_issue.eo = epi_prefetch<EPI>(a, nb, f1, o8);
-                }
+                f1 = syn24_stream(t + 1);
+                prefetch(pv, fp, var_base(f1), tid);
             }
-            if (s < 0) {                      // gradient-only pass
-                const double gx = d1_at(T, c, 1, ih), gy = d1_at(T, c, RS, ih), gz = d1_at(T, c, PS, ih);
-                if (sub == 0) { n0x = gx; n0y = gy; n0z = gz; }
-                else if (sub == 1) { n1x = gx; n1y = gy; n1z = gz; }
-                else { n2x = gx; n2y = gy; n2z = gz; }
-            } else if (sub == 0) {
-                const Syn24Part p = syn24_axes<true>(T, c, wy, wz, owny, ownz, n0x, n0y, n0z, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
-                Mixed mx;
-                if (OCTFD_SKIP & 1) { mx.dxy = p.t1; mx.dxz = p.t3q; mx.dyz = p.ko; }
-                else mx = mixed_derivs(T, wy, wz, tid, owny, ownz, ih);
-                double off = Gxy * mx.dxy;
-                off = fma(Gxz, mx.dxz, off);
-                off = fma(Gyz, mx.dyz, off);
-                lap = fma(2.0, off, p.diag);
-                emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l_use.unext), l_use.eo);
-            } else {
-                Syn24Part p;
-                if (sub == 1) p = syn24_axes<false>(T, c, wy, wz, owny, ownz, n1x, n1y, n1z, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
-                else p = syn24_axes<false>(T, c, wy, wz, owny, ownz, n2x, n2y, n2z, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
-                emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l_use.unext), l_use.eo);
-            }
-            if (t + 1 < NSTREAM) commit<ZIN>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, p_commit, var_base(f1), tid);
+            l.unext = centre((f + 11) % 24);
+            l.eo = epi_prefetch<EPI>(a, nb, f, o8);
+            if (t > 10) l.lap = ldg(stash_base(10 + f % 10), s8);
+        };
+        // pass over a variable with second derivatives (9..0)
+        auto pass_d2 = [&](int t) {
+            const double* T = tiles + (t & 1) * TILE;
+            const int f = syn24_stream(t);
+            int f1 = 0;
+            Look l{0.0, 0.0, {0.0, 0.0}};
+            issue(t, f, l, f1);
+            const Syn24Part p = syn24_axes<true>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
+            Mixed mx;
+            if (OCTFD_SKIP & 1) { mx.dxy = p.t1; mx.dxz = p.t3q; mx.dyz = p.ko; }
+            else mx = mixed_derivs(T, wy, wz, tid, owny, ownz, ih);
+            double off = Gxy * mx.dxy;
+            off = fma(Gxz, mx.dxz, off);
+            off = fma(Gyz, mx.dyz, off);
+            const double lap = fma(2.0, off, p.diag);
+            stg(stash_base(10 + f), s8, lap);
+            emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l.unext), l.eo);
+            commit<ZIN>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, var_base(f1), tid);
             __syncthreads();
         };
+        // pass over a variable without second derivatives (23..10)
+        auto pass_light = [&](int t) {
+            const double* T = tiles + (t & 1) * TILE;
+            const int f = syn24_stream(t);
+            int f1 = 0;
+            Look l{0.0, 0.0, {0.0, 0.0}};
+            issue(t, f, l, f1);
+            const Syn24Part p = syn24_axes<false>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
+            emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, l.lap, halpha, l.unext), l.eo);
+            if (t + 1 < NSTREAM) {
+                commit<ZIN>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, var_base(f1), tid);
+                __syncthreads();
+            }
+        };
 
-        {
-            int f, s, sub;
-            syn24_stream(0, f, s, sub);
+        {   // pass 0: gradient of variable 10 only
+            const int f = syn24_stream(0), f1 = syn24_stream(1);
             prefetch(pv, fp, var_base(f), tid);
             commit<ZIN>(tiles, scratch, bi, fp, pv, var_base(f), tid);
-            syn24_stream(1, f, s, sub);
-            prefetch(pv1, fp, var_base(f), tid);
+            __syncthreads();
+            prefetch(pv, fp, var_base(f1), tid);
+            nx = d1_at(tiles, c, 1, ih); ny = d1_at(tiles, c, RS, ih); nz = d1_at(tiles, c, PS, ih);
+            commit<ZIN>(tiles + TILE, scratch, bi, fp, pv, var_base(f1), tid);
             __syncthreads();
         }
 #pragma unroll 1
-        for (int t = 0; t < NSTREAM; t += 2) {
-            pass(t, pv, pv1, lk1, lk0);
-            if (t + 1 < NSTREAM) pass(t + 1, pv1, pv, lk0, lk1);
-        }
+        for (int t = 1; t <= 10; ++t) pass_d2(t);
+#pragma unroll 1
+        for (int t = 11; t < NSTREAM; ++t) pass_light(t);
     }
 }
 

@@ -29,6 +29,8 @@ struct RhsArgs {
     double* out;        // kOutPadded / kOutZipped: result; kRkFirst / kRkMiddle: next stage vector
     double* acc;        // Runge-Kutta accumulator (zipped)
     double* u;          // state at the start of the step (zipped); written by kRkLast
+    double* stash;      // SYN24 only: array shaped like `out` whose variables 10..19 may be used as
+                        // scratch until their final values are written (may be `out` itself)
     double c;           // dt/2, dt or dt/6
     double sigma;       // Kreiss-Oliger strength
 };

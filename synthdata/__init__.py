@@ -97,6 +97,8 @@ CONFIGS = {
                radius_q20=[104857, 87031, 72236, 59956, 49763, 41303], kind="SYN24", field="gauss24"),
     # uniform tree of 32,768 blocks: no level jumps at all (isolates the cost of ghost interpolation)
     "U5": dict(lmin=5, lmax=5, style="rand", radius_q20=[], kind="SYN24", field="gauss24"),
+    "U4": dict(lmin=4, lmax=4, style="rand", radius_q20=[], kind="SYN24", field="gauss24"),
+    "U6": dict(lmin=6, lmax=6, style="rand", radius_q20=[], kind="SYN24", field="gauss24"),
     # small trees of the same shape, for element-by-element parity in seconds
     "T2": dict(lmin=3, lmax=5, style="rand", radius_q20=[60000, 40000], kind="DERIVS", field="sine"),
     "T3": dict(lmin=3, lmax=5, style="rand", radius_q20=[60000, 40000], kind="WAVE", field="pulse"),

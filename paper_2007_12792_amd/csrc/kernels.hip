@@ -16,6 +16,8 @@
 // -ffp-contract=off, so a fused multiply-add happens exactly where fma() is written.
 #include "kernels.hpp"
 
+#include <type_traits>
+
 namespace octfd {
 namespace {
 
@@ -109,33 +111,75 @@ __device__ __forceinline__ void load_block_info(BlockInfo& bi, const DeviceTree&
 
 // ---------------------------------------------------------------- fill plan
 
-constexpr int PLAN = (PBLK + NTHREADS - 1) / NTHREADS;   // 6 tile entries per thread
+// The 2,744 points of the tile are enumerated so that a prefix of the enumeration is exactly what a
+// kernel needs:
+//   [0, NFACE)      interior and the six face slabs: all that stencils along the axes read;
+//   [NFACE, NEDGE)  the twelve edge slabs: read in addition by the mixed second derivatives;
+//   [NEDGE, PBLK)   the eight corners: needed only when the whole padded block is written out.
+// Fetching only the prefix in use matters because every ghost row is its own cache line in the
+// neighbour's zipped storage: faces alone touch 288 lines per tile, the full tile 588.
+constexpr int NFACE = BLK + 6 * PAD * NPT * NPT;                 // 1664
+constexpr int NEDGE = NFACE + 12 * PAD * PAD * NPT;              // 2528
+constexpr int PLAN_FACE = (NFACE + NTHREADS - 1) / NTHREADS;     // 4 entries per thread
+constexpr int PLAN_EDGE = (NEDGE + NTHREADS - 1) / NTHREADS;     // 5
+constexpr int PLAN_FULL = (PBLK + NTHREADS - 1) / NTHREADS;      // 6
 
-// Entries with nothing to copy (beyond the tile, or interpolated later) read element 0 and write
-// to DUMMY, a padding slot of the tile that no stencil reads; the copy loop is branch-free.
+__device__ __forceinline__ int ghost_index(int g) { return g < PAD ? g : g + NPT; }   // 0,1,2,11,12,13
+
+__device__ __forceinline__ void tile_point(int p, int& ii, int& jj, int& kk)
+{
+    if (p < 14 * 64) {                               // x-extended interior rows
+        const int r = p / NP;
+        ii = p - r * NP; jj = PAD + (r & 7); kk = PAD + (r >> 3);
+    } else if (p < 14 * 64 + 384) {                  // y faces
+        const int q = p - 14 * 64, r = q >> 3, kq = r / 6;
+        ii = PAD + (q & 7); jj = ghost_index(r - 6 * kq); kk = PAD + kq;
+    } else if (p < NFACE) {                          // z faces
+        const int q = p - (14 * 64 + 384);
+        ii = PAD + (q & 7); jj = PAD + ((q >> 3) & 7); kk = ghost_index(q >> 6);
+    } else if (p < NFACE + 288) {                    // xy edges
+        const int q = p - NFACE, r = q / 6, kq = r / 6;
+        ii = ghost_index(q - 6 * r); jj = ghost_index(r - 6 * kq); kk = PAD + kq;
+    } else if (p < NFACE + 576) {                    // xz edges
+        const int q = p - (NFACE + 288), r = q / 6;
+        ii = ghost_index(q - 6 * r); jj = PAD + (r & 7); kk = ghost_index(r >> 3);
+    } else if (p < NEDGE) {                          // yz edges
+        const int q = p - (NFACE + 576), r = q >> 3, kq = r / 6;
+        ii = PAD + (q & 7); jj = ghost_index(r - 6 * kq); kk = ghost_index(kq);
+    } else {                                         // corners
+        const int q = p - NEDGE, r = q / 6, kq = r / 6;
+        ii = ghost_index(q - 6 * r); jj = ghost_index(r - 6 * kq); kk = ghost_index(kq);
+    }
+}
+
+// Entries with nothing to copy (beyond the range in use, or interpolated later) read element 0 and
+// write to DUMMY, a padding slot of the tile that no stencil reads; the copy loop is branch-free.
 constexpr int DUMMY = NP * RS;   // first padding slot behind plane 0
 // src: byte offset in the source array, kept in LDS as src[m * NTHREADS + tid] (it is needed once
 // per variable and registers are scarce); dst: tile index, two 16-bit values per register
+template <int NPLAN>
 struct FillPlan {
     uint32_t* src;
-    uint32_t dstp[PLAN / 2];
+    uint32_t dstp[(NPLAN + 1) / 2];
     __device__ __forceinline__ int dst(int m) const { return (dstp[m >> 1] >> (16 * (m & 1))) & 0xffff; }
     __device__ __forceinline__ void set_dst(int m, int v) { dstp[m >> 1] = (m & 1) ? (dstp[m >> 1] | ((uint32_t)v << 16)) : (uint32_t)v; }
 };
-static_assert(PLAN % 2 == 0 && TILE < 65536, "tile indices are packed in pairs");
+static_assert(TILE < 65536, "tile indices are packed in pairs");
 
 // Source of every padded point this thread fills, as a byte offset into one variable's zipped
 // array (same-level copy or injection from a finer leaf).  Points whose source is coarser are left
-// to the interpolation passes.
-__device__ __forceinline__ void make_plan_zipped(FillPlan& fp, const BlockInfo& bi, int tid)
+// to the interpolation passes.  NPOINTS = how long a prefix of the enumeration is planned.
+template <int NPLAN, int NPOINTS>
+__device__ __forceinline__ void make_plan_zipped(FillPlan<NPLAN>& fp, const BlockInfo& bi, int tid)
 {
 #pragma unroll
-    for (int m = 0; m < PLAN; ++m) {
+    for (int m = 0; m < NPLAN; ++m) {
         const int p = tid + m * NTHREADS;
         uint32_t src = 0;
         int dst = DUMMY;
-        if (p < PBLK) {
-            const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
+        if (p < NPOINTS) {
+            int ii, jj, kk;
+            tile_point(p, ii, jj, kk);
             const int rx = ii < PAD ? 0 : (ii < PAD + NPT ? 1 : 2);
             const int ry = jj < PAD ? 0 : (jj < PAD + NPT ? 1 : 2);
             const int rz = kk < PAD ? 0 : (kk < PAD + NPT ? 1 : 2);
@@ -167,14 +211,17 @@ __device__ __forceinline__ void make_plan_zipped(FillPlan& fp, const BlockInfo& 
     }
 }
 
-__device__ __forceinline__ void make_plan_padded(FillPlan& fp, int tid)
+// same for a padded source block (plain copy)
+template <int NPLAN, int NPOINTS>
+__device__ __forceinline__ void make_plan_padded(FillPlan<NPLAN>& fp, int tid)
 {
 #pragma unroll
-    for (int m = 0; m < PLAN; ++m) {
+    for (int m = 0; m < NPLAN; ++m) {
         const int p = tid + m * NTHREADS;
-        const bool ok = p < PBLK;
-        const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
-        fp.src[m * NTHREADS + tid] = ok ? p * 8u : 0u;
+        const bool ok = p < NPOINTS;
+        int ii, jj, kk;
+        tile_point(ok ? p : 0, ii, jj, kk);
+        fp.src[m * NTHREADS + tid] = ok ? (uint32_t)((kk * NP + jj) * NP + ii) * 8u : 0u;
         fp.set_dst(m, ok ? tidx(kk, jj, ii) : DUMMY);
     }
 }
@@ -201,65 +248,95 @@ __device__ __forceinline__ double interp_line(const double* v, int st, int f, co
 __device__ __forceinline__ uint32_t div_magic(uint32_t d) { return 0xffffffffu / d + 1u; }
 __device__ __forceinline__ int div_by(int q, uint32_t magic) { return (int)__umulhi((uint32_t)q, magic); }
 
+// Interpolate one box [sx,sx+nx) x [sy,sy+ny) x [sz,sz+nz) of the tile from coarser leaf `id`:
+// x pass, y pass, z pass through LDS staging.  Uniform control flow; starts with a barrier (the
+// staging arrays may still be in use) and ends without one.
+__device__ __forceinline__ void interp_box(double* tile, double* scratch, const BlockInfo& bi, const double* __restrict__ base,
+                                           int32_t id, int sx, int nx, int sy, int ny, int sz, int nz, int tid)
+{
+    double* T1 = scratch;            // after the x pass  [cz][cy][tx], row stride NP
+    double* T2 = T1 + T1N;           // after the y pass  [cz][ty][tx]
+    double* C = T2;                  // the coarse leaf, 8^3: dead once the x pass is done
+    const uint32_t mx = div_magic(nx), mxy = div_magic(nx * ny);
+    // fine coordinate of the box's first point inside the coarse leaf (aligned to 16 points)
+    const int fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
+    const int fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
+    const int fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
+    const double cval = ldg(base, ((uint32_t)id * BLK + tid) * 8u);
+    __syncthreads();                 // everybody is done with the staging arrays (C overlays T2)
+    C[tid] = cval;
+    __syncthreads();
+    for (int q = tid; q < 64 * nx; q += NTHREADS) {              // x pass
+        const int row = div_by(q, mx), tx = q - row * nx;        // row = cz*8 + cy
+        T1[row * NP + tx] = interp_line(&C[row * NPT], 1, fx0 + tx, bi.lag);
+    }
+    __syncthreads();
+    for (int q = tid; q < NPT * ny * nx; q += NTHREADS) {        // y pass
+        const int cz = div_by(q, mxy), r = q - cz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
+        T2[(cz * NP + ty) * NP + tx] = interp_line(&T1[cz * NPT * NP + tx], NP, fy0 + ty, bi.lag);
+    }
+    __syncthreads();
+    for (int q = tid; q < nz * ny * nx; q += NTHREADS) {         // z pass, into the tile
+        const int tz = div_by(q, mxy), r = q - tz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
+        tile[tidx(sz + tz, sy + ty, sx + tx)] = interp_line(&T2[ty * NP + tx], NP * NP, fz0 + tz, bi.lag);
+    }
+}
+
 // Filling the tile of one variable is split in two so that the global loads of the next variable
 // can be in flight while the current one is being differentiated:
 //   prefetch(): issue the planned loads into registers;
-//   commit():   store them into a tile buffer, then (zipped input only) interpolate the boxes whose
-//               source leaf is coarser.  `base` is that variable's zipped array (ZIN) or this
-//               block's padded data.  All threads call both.  commit() does NOT end with a barrier.
-__device__ __forceinline__ void prefetch(double (&v)[PLAN], const FillPlan& fp, const double* __restrict__ base, int tid)
+//   commit():   store them into a tile buffer, then (zipped input only) interpolate what comes from
+//               coarser leaves.  `base` is that variable's zipped array (ZIN) or this block's padded
+//               data.  All threads call both.  commit() does NOT end with a barrier.
+// USE = how many plan entries per thread are in use (PLAN_FACE: faces only).
+template <int NPLAN, int USE>
+__device__ __forceinline__ void prefetch(double (&v)[NPLAN], const FillPlan<NPLAN>& fp, const double* __restrict__ base, int tid)
 {
-    uint32_t off[PLAN];
+    uint32_t off[USE];
 #pragma unroll
-    for (int m = 0; m < PLAN; ++m) off[m] = fp.src[m * NTHREADS + tid];
+    for (int m = 0; m < USE; ++m) off[m] = fp.src[m * NTHREADS + tid];
+    // the last entry in use may reach beyond the face prefix: read element 0 instead
+    if (USE == PLAN_FACE && NPLAN > PLAN_FACE && tid + (USE - 1) * NTHREADS >= NFACE) off[USE - 1] = 0;
 #pragma unroll
-    for (int m = 0; m < PLAN; ++m) v[m] = (OCTFD_SKIP & 2) ? 1.0 : ldg(base, off[m]);
+    for (int m = 0; m < USE; ++m) v[m] = (OCTFD_SKIP & 2) ? 1.0 : ldg(base, off[m]);
 }
 
-template <bool ZIN>
-__device__ __forceinline__ void commit(double* tile, double* scratch, const BlockInfo& bi, const FillPlan& fp,
-                                       const double (&v)[PLAN], const double* __restrict__ base, int tid)
+template <bool ZIN, int NPLAN, int USE>
+__device__ __forceinline__ void commit(double* tile, double* scratch, const BlockInfo& bi, const FillPlan<NPLAN>& fp,
+                                       const double (&v)[NPLAN], const double* __restrict__ base, int tid)
 {
 #pragma unroll
-    for (int m = 0; m < PLAN; ++m) tile[fp.dst(m)] = v[m];
-    if (ZIN && bi.cs[0] >= 0) {
-        // every coarser source leaf covers a box of the padded block; interpolate box by box,
-        // x then y then z.  Control flow is uniform over the workgroup.  The staging arrays share
-        // LDS with the mixed-derivative arrays, which other wavefronts may still be reading.
-        double* T1 = scratch;            // after the x pass  [cz][cy][tx], row stride NP
-        double* T2 = T1 + T1N;           // after the y pass  [cz][ty][tx]
-        double* C = T2;                  // the coarse leaf, 8^3: dead once the x pass is done
+    for (int m = 0; m < USE; ++m) {
+        int d = fp.dst(m);
+        if (USE == PLAN_FACE && NPLAN > PLAN_FACE && m == USE - 1 && tid + m * NTHREADS >= NFACE) d = DUMMY;
+        tile[d] = v[m];
+    }
+    if (!ZIN || bi.cs[0] < 0) return;
+    // Control flow below is uniform over the workgroup.
+    if (USE == PLAN_FACE) {
+        // faces only: each of the six face neighbours that is coarser supplies a 3 x 8 x 8 slab
+#pragma unroll 1
+        for (int face = 0; face < 6; ++face) {
+            const int ax = face >> 1, hi = face & 1;
+            const int dir = 13 + (hi ? 1 : -1) * (ax == 0 ? 1 : (ax == 1 ? 3 : 9));
+            if (bi.gt[dir * 5] != K_COARSER) continue;
+            const int s0 = hi ? PAD + NPT : 0;
+            interp_box(tile, scratch, bi, base, bi.gt[dir * 5 + 1],
+                       ax == 0 ? s0 : PAD, ax == 0 ? PAD : NPT, ax == 1 ? s0 : PAD, ax == 1 ? PAD : NPT,
+                       ax == 2 ? s0 : PAD, ax == 2 ? PAD : NPT, tid);
+        }
+    } else {
+        // every coarser source leaf covers a box of the padded block
+#pragma unroll 1
         for (int sidx = 0; sidx < 8; ++sidx) {
             const int32_t id = bi.cs[2 * sidx];
             if (id < 0) break;
-            __syncthreads();             // everybody is done with the staging arrays (C overlays T2)
             const int pk = bi.cs[2 * sidx + 1];
             const int rxl = pk & 3, rxh = (pk >> 2) & 3, ryl = (pk >> 4) & 3, ryh = (pk >> 6) & 3, rzl = (pk >> 8) & 3, rzh = (pk >> 10) & 3;
             const int sx = rxl == 0 ? 0 : (rxl == 1 ? PAD : PAD + NPT), ex = rxh == 0 ? PAD : (rxh == 1 ? PAD + NPT : NP);
             const int sy = ryl == 0 ? 0 : (ryl == 1 ? PAD : PAD + NPT), ey = ryh == 0 ? PAD : (ryh == 1 ? PAD + NPT : NP);
             const int sz = rzl == 0 ? 0 : (rzl == 1 ? PAD : PAD + NPT), ez = rzh == 0 ? PAD : (rzh == 1 ? PAD + NPT : NP);
-            const int nx = ex - sx, ny = ey - sy, nz = ez - sz;
-            const uint32_t mx = div_magic(nx), mxy = div_magic(nx * ny);
-            // fine coordinate of the box's first point inside the coarse leaf (aligned to 16 points)
-            const int fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
-            const int fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
-            const int fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
-            C[tid] = ldg(base, ((uint32_t)id * BLK + tid) * 8u);
-            __syncthreads();
-            for (int q = tid; q < 64 * nx; q += NTHREADS) {              // x pass
-                const int row = div_by(q, mx), tx = q - row * nx;        // row = cz*8 + cy
-                T1[row * NP + tx] = interp_line(&C[row * NPT], 1, fx0 + tx, bi.lag);
-            }
-            __syncthreads();
-            for (int q = tid; q < NPT * ny * nx; q += NTHREADS) {        // y pass
-                const int cz = div_by(q, mxy), r = q - cz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
-                T2[(cz * NP + ty) * NP + tx] = interp_line(&T1[cz * NPT * NP + tx], NP, fy0 + ty, bi.lag);
-            }
-            __syncthreads();
-            for (int q = tid; q < nz * ny * nx; q += NTHREADS) {         // z pass, into the tile
-                const int tz = div_by(q, mxy), r = q - tz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
-                tile[tidx(sz + tz, sy + ty, sx + tx)] = interp_line(&T2[ty * NP + tx], NP * NP, fz0 + tz, bi.lag);
-            }
+            interp_box(tile, scratch, bi, base, id, sx, ex - sx, sy, ey - sy, sz, ez - sz, tid);
         }
     }
 }
@@ -357,7 +434,7 @@ __device__ __forceinline__ Mixed mixed_derivs(const double* tile, double* wy, do
         const int ct = tidx(lb + PAD, jj, la + PAD);
         wz[lb * PS + jj * RS + (la + PAD)] = d1_at(tile, ct, PS, ih);
     }
-    __syncthreads();
+    if (!(OCTFD_SKIP & 128)) __syncthreads();
     Mixed r;
     r.dxy = d1_at(wy, owny, 1, ih);
     __builtin_amdgcn_sched_barrier(0);
@@ -475,7 +552,10 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
     __shared__ double tiles[NBUF * TILE];
     __shared__ double scratch[(ZIN || KIND == OT_RHS_SYN24) ? SCRATCH : 1];
     __shared__ BlockInfo bi;
-    __shared__ uint32_t plan_src[PLAN * NTHREADS];
+    // second derivatives (SYN24 only) read the edge slabs of the tile too
+    constexpr int NPLAN = KIND == OT_RHS_SYN24 ? PLAN_EDGE : PLAN_FACE;
+    constexpr int NPOINTS = KIND == OT_RHS_SYN24 ? NEDGE : NFACE;
+    __shared__ uint32_t plan_src[NPLAN * NTHREADS];
 
     const int tid = threadIdx.x;
     const int64_t nb = tr.nb;
@@ -495,20 +575,19 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
     const double ih = (double)(NPT << bi.level), ih2 = ih * ih;
     const double sigma = a.sigma;
 
-    FillPlan fp;
+    FillPlan<NPLAN> fp;
     fp.src = plan_src;
-    if (ZIN) make_plan_zipped(fp, bi, tid);
-    else make_plan_padded(fp, tid);
-    double pv[PLAN];
-    if (OCTFD_SKIP & 64) { tiles[tid] = (double)(fp.dstp[0] + fp.dstp[1] + fp.dstp[2]); return; }   // timing experiment: + plan
+    if (ZIN) make_plan_zipped<NPLAN, NPOINTS>(fp, bi, tid);
+    else make_plan_padded<NPLAN, NPOINTS>(fp, tid);
+    double pv[NPLAN];
 
     auto var_base = [&](int v) -> const double* {
         return ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK;
     };
     auto stage = [&](int v) {   // bring variable v into tile buffer 0 (barrier before and after)
         __syncthreads();
-        prefetch(pv, fp, var_base(v), tid);
-        commit<ZIN>(tiles, scratch, bi, fp, pv, var_base(v), tid);
+        prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(v), tid);
+        commit<ZIN, NPLAN, PLAN_FACE>(tiles, scratch, bi, fp, pv, var_base(v), tid);
         __syncthreads();
     };
     auto centre = [&](int v) -> double {   // this thread's own value of variable v
@@ -563,23 +642,28 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
         };
         const uint32_t s8 = EPI == kOutPadded ? p8 : o8;
 
-        // top of pass t: request the tile data of pass t+1 and this pass's own pointwise operands
-        auto issue = [&](int t, int f, Look& l, int& f1) {
+        // top of pass t: request the tile data of pass t+1 and this pass's own pointwise operands.
+        // NEXT_USE says how much of the tile pass t+1 reads (edges only if it takes second derivatives).
+        auto issue = [&](int t, int f, Look& l, int& f1, auto next_use) {
+            constexpr int NEXT_USE = decltype(next_use)::value;
             if (t + 1 < NSTREAM) {
                 f1 = syn24_stream(t + 1);
-                prefetch(pv, fp, var_base(f1), tid);
+                prefetch<NPLAN, NEXT_USE>(pv, fp, var_base(f1), tid);
             }
             l.unext = centre((f + 11) % 24);
             l.eo = epi_prefetch<EPI>(a, nb, f, o8);
             if (t > 10) l.lap = ldg(stash_base(10 + f % 10), s8);
         };
+        using UseEdge = std::integral_constant<int, PLAN_EDGE>;
+        using UseFace = std::integral_constant<int, PLAN_FACE>;
         // pass over a variable with second derivatives (9..0)
-        auto pass_d2 = [&](int t) {
+        auto pass_d2 = [&](int t, auto next_use) {
+            constexpr int NEXT_USE = decltype(next_use)::value;
             const double* T = tiles + (t & 1) * TILE;
             const int f = syn24_stream(t);
             int f1 = 0;
             Look l{0.0, 0.0, {0.0, 0.0}};
-            issue(t, f, l, f1);
+            issue(t, f, l, f1, next_use);
             const Syn24Part p = syn24_axes<true>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
             Mixed mx;
             if (OCTFD_SKIP & 1) { mx.dxy = p.t1; mx.dxz = p.t3q; mx.dyz = p.ko; }
@@ -590,8 +674,8 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
             const double lap = fma(2.0, off, p.diag);
             stg(stash_base(10 + f), s8, lap);
             emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l.unext), l.eo);
-            commit<ZIN>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, var_base(f1), tid);
-            __syncthreads();
+            commit<ZIN, NPLAN, NEXT_USE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, var_base(f1), tid);
+            if (!(OCTFD_SKIP & 128)) __syncthreads();
         };
         // pass over a variable without second derivatives (23..10)
         auto pass_light = [&](int t) {
@@ -599,27 +683,28 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
             const int f = syn24_stream(t);
             int f1 = 0;
             Look l{0.0, 0.0, {0.0, 0.0}};
-            issue(t, f, l, f1);
+            issue(t, f, l, f1, UseFace{});
             const Syn24Part p = syn24_axes<false>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
             emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, l.lap, halpha, l.unext), l.eo);
             if (t + 1 < NSTREAM) {
-                commit<ZIN>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, var_base(f1), tid);
-                __syncthreads();
+                commit<ZIN, NPLAN, PLAN_FACE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, var_base(f1), tid);
+                if (!(OCTFD_SKIP & 128)) __syncthreads();
             }
         };
 
         {   // pass 0: gradient of variable 10 only
             const int f = syn24_stream(0), f1 = syn24_stream(1);
-            prefetch(pv, fp, var_base(f), tid);
-            commit<ZIN>(tiles, scratch, bi, fp, pv, var_base(f), tid);
+            prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(f), tid);
+            commit<ZIN, NPLAN, PLAN_FACE>(tiles, scratch, bi, fp, pv, var_base(f), tid);
             __syncthreads();
-            prefetch(pv, fp, var_base(f1), tid);
+            prefetch<NPLAN, PLAN_EDGE>(pv, fp, var_base(f1), tid);
             nx = d1_at(tiles, c, 1, ih); ny = d1_at(tiles, c, RS, ih); nz = d1_at(tiles, c, PS, ih);
-            commit<ZIN>(tiles + TILE, scratch, bi, fp, pv, var_base(f1), tid);
+            commit<ZIN, NPLAN, PLAN_EDGE>(tiles + TILE, scratch, bi, fp, pv, var_base(f1), tid);
             __syncthreads();
         }
 #pragma unroll 1
-        for (int t = 1; t <= 10; ++t) pass_d2(t);
+        for (int t = 1; t < 10; ++t) pass_d2(t, UseEdge{});
+        pass_d2(10, UseFace{});
 #pragma unroll 1
         for (int t = 11; t < NSTREAM; ++t) pass_light(t);
     }
@@ -632,21 +717,21 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, const double*
     __shared__ double tile[TILE];
     __shared__ double scratch[SCRATCH];
     __shared__ BlockInfo bi;
-    __shared__ uint32_t plan_src[PLAN * NTHREADS];
+    __shared__ uint32_t plan_src[PLAN_FULL * NTHREADS];
     const int tid = threadIdx.x;
     const int64_t b = blockIdx.x, v = blockIdx.y, nb = tr.nb;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
-    FillPlan fp;
+    FillPlan<PLAN_FULL> fp;
     fp.src = plan_src;
-    make_plan_zipped(fp, bi, tid);
-    double pv[PLAN];
-    prefetch(pv, fp, zipped + v * nb * BLK, tid);
-    commit<true>(tile, scratch, bi, fp, pv, zipped + v * nb * BLK, tid);
+    make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);
+    double pv[PLAN_FULL];
+    prefetch<PLAN_FULL, PLAN_FULL>(pv, fp, zipped + v * nb * BLK, tid);
+    commit<true, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, zipped + v * nb * BLK, tid);
     __syncthreads();
     double* out = padded + (v * nb + b) * PBLK;
 #pragma unroll
-    for (int m = 0; m < PLAN; ++m) {
+    for (int m = 0; m < PLAN_FULL; ++m) {
         const int p = tid + m * NTHREADS;
         const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
         if (p < PBLK) out[p] = tile[tidx(kk, jj, ii)];

@@ -55,7 +55,8 @@ __constant__ double c_lag[36] = {
 
 struct BlockInfo {       // per-workgroup copy of the block's table rows
     int32_t gt[27 * 5];
-    int32_t cs[16];      // coarse sources: {leaf id, packed region range} x 8, id < 0 ends the list
+    int32_t cs[32];      // [0..15] coarse sources: {leaf id, packed region range} x 8, id < 0 ends the
+                         // list; [16] number of coarser faces, [17..28] {face, leaf id} pairs
     uint32_t level, ax, ay, az;
     double lag[36];
 };
@@ -102,7 +103,7 @@ __device__ __forceinline__ void load_block_info(BlockInfo& bi, const DeviceTree&
 {
     if (tid < 27 * 5) bi.gt[tid] = tr.ghost[b * (27 * 5) + tid];
     if (tid >= 192 && tid < 192 + 36) bi.lag[tid - 192] = c_lag[tid - 192];
-    if (tid >= 256 && tid < 256 + 16) bi.cs[tid - 256] = tr.coarse[b * 16 + (tid - 256)];
+    if (tid >= 256 && tid < 256 + 32) bi.cs[tid - 256] = tr.coarse[b * 32 + (tid - 256)];
     if (tid == 320) {
         const ot_leaf lf = tr.leaves[b];
         bi.level = lf.level; bi.ax = lf.ix; bi.ay = lf.iy; bi.az = lf.iz;
@@ -165,6 +166,7 @@ struct FillPlan {
     __device__ __forceinline__ void set_dst(int m, int v) { dstp[m >> 1] = (m & 1) ? (dstp[m >> 1] | ((uint32_t)v << 16)) : (uint32_t)v; }
 };
 static_assert(TILE < 65536, "tile indices are packed in pairs");
+static_assert(SCRATCH >= 1024 + 2 * 512, "face interpolation staging: 8 x 128 per-wavefront + 2 x 512 shared");
 
 // Source of every padded point this thread fills, as a byte offset into one variable's zipped
 // array (same-level copy or injection from a finer leaf).  Points whose source is coarser are left
@@ -248,11 +250,12 @@ __device__ __forceinline__ double interp_line(const double* v, int st, int f, co
 __device__ __forceinline__ uint32_t div_magic(uint32_t d) { return 0xffffffffu / d + 1u; }
 __device__ __forceinline__ int div_by(int q, uint32_t magic) { return (int)__umulhi((uint32_t)q, magic); }
 
-// Interpolate one box [sx,sx+nx) x [sy,sy+ny) x [sz,sz+nz) of the tile from coarser leaf `id`:
+// Interpolate one box [sx,sx+nx) x [sy,sy+ny) x [sz,sz+nz) of the tile from a coarser leaf:
 // x pass, y pass, z pass through LDS staging.  Uniform control flow; starts with a barrier (the
 // staging arrays may still be in use) and ends without one.
-__device__ __forceinline__ void interp_box(double* tile, double* scratch, const BlockInfo& bi, const double* __restrict__ base,
-                                           int32_t id, int sx, int nx, int sy, int ny, int sz, int nz, int tid)
+// cval = this thread's element (index tid) of the coarse leaf's 8^3 values.
+__device__ __forceinline__ void interp_box(double* tile, double* scratch, const BlockInfo& bi, double cval,
+                                           int sx, int nx, int sy, int ny, int sz, int nz, int tid)
 {
     double* T1 = scratch;            // after the x pass  [cz][cy][tx], row stride NP
     double* T2 = T1 + T1N;           // after the y pass  [cz][ty][tx]
@@ -262,7 +265,6 @@ __device__ __forceinline__ void interp_box(double* tile, double* scratch, const 
     const int fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
     const int fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
     const int fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
-    const double cval = ldg(base, ((uint32_t)id * BLK + tid) * 8u);
     __syncthreads();                 // everybody is done with the staging arrays (C overlays T2)
     C[tid] = cval;
     __syncthreads();
@@ -301,9 +303,22 @@ __device__ __forceinline__ void prefetch(double (&v)[NPLAN], const FillPlan<NPLA
     for (int m = 0; m < USE; ++m) v[m] = (OCTFD_SKIP & 2) ? 1.0 : ldg(base, off[m]);
 }
 
+// Values of the coarser face neighbours can be requested together with the tile data
+// (coarse_prefetch) so that their latency hides behind the stencil work: CPRE slots, in the order of
+// the block's coarse-face list; further faces are loaded late.
+constexpr int CPRE = 3;
+__device__ __forceinline__ void coarse_prefetch(double (&cv)[CPRE], const BlockInfo& bi, const double* __restrict__ base, int tid)
+{
+    const int n = bi.cs[16];
+#pragma unroll
+    for (int q = 0; q < CPRE; ++q)
+        if (q < n) cv[q] = ldg(base, ((uint32_t)bi.cs[18 + 2 * q] * BLK + tid) * 8u);
+}
+
 template <bool ZIN, int NPLAN, int USE>
 __device__ __forceinline__ void commit(double* tile, double* scratch, const BlockInfo& bi, const FillPlan<NPLAN>& fp,
-                                       const double (&v)[NPLAN], const double* __restrict__ base, int tid)
+                                       const double (&v)[NPLAN], const double (&cv)[CPRE], bool have_cv,
+                                       const double* __restrict__ base, int tid)
 {
 #pragma unroll
     for (int m = 0; m < USE; ++m) {
@@ -314,16 +329,44 @@ __device__ __forceinline__ void commit(double* tile, double* scratch, const Bloc
     if (!ZIN || bi.cs[0] < 0) return;
     // Control flow below is uniform over the workgroup.
     if (USE == PLAN_FACE) {
-        // faces only: each of the six face neighbours that is coarser supplies a 3 x 8 x 8 slab
+        // Faces only: each face neighbour that is coarser supplies a 3 x 8 x 8 slab.  Wavefront w
+        // owns the coarse plane cz = w: it interpolates that plane in x and then in y out of its
+        // own staging area with no workgroup barrier; only the z pass, which combines the planes,
+        // needs one.  The y-pass results are double-buffered across faces.
+        const int n = bi.cs[16];
+        const int wave = tid >> 6, lane = tid & 63;
+        double* Cs = scratch + wave * 128;       // this wavefront's coarse plane, [cy][cx]
+        double* T1s = Cs + 64;                   // after the x pass, [cy][tx]
+        __syncthreads();                         // the staging arrays may still be read as wy / wz
 #pragma unroll 1
-        for (int face = 0; face < 6; ++face) {
-            const int ax = face >> 1, hi = face & 1;
-            const int dir = 13 + (hi ? 1 : -1) * (ax == 0 ? 1 : (ax == 1 ? 3 : 9));
-            if (bi.gt[dir * 5] != K_COARSER) continue;
-            const int s0 = hi ? PAD + NPT : 0;
-            interp_box(tile, scratch, bi, base, bi.gt[dir * 5 + 1],
-                       ax == 0 ? s0 : PAD, ax == 0 ? PAD : NPT, ax == 1 ? s0 : PAD, ax == 1 ? PAD : NPT,
-                       ax == 2 ? s0 : PAD, ax == 2 ? PAD : NPT, tid);
+        for (int q = 0; q < n; ++q) {
+            const int face = bi.cs[17 + 2 * q], ax = face >> 1, s0 = (face & 1) ? PAD + NPT : 0;
+            const int sx = ax == 0 ? s0 : PAD, sy = ax == 1 ? s0 : PAD, sz = ax == 2 ? s0 : PAD;
+            const int nx = ax == 0 ? PAD : NPT, ny = ax == 1 ? PAD : NPT, nz = ax == 2 ? PAD : NPT;
+            const uint32_t mx = div_magic(nx), mxy = div_magic(nx * ny);
+            const int fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
+            const int fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
+            const int fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
+            double* T2 = scratch + 1024 + (q & 1) * 512;   // after the y pass, [cz][ty][tx], 64 per plane
+            double cval;
+            if (have_cv && q < CPRE) cval = q == 0 ? cv[0] : (q == 1 ? cv[1] : cv[2]);
+            else cval = ldg(base, ((uint32_t)bi.cs[18 + 2 * q] * BLK + tid) * 8u);
+            Cs[lane] = cval;
+            __builtin_amdgcn_wave_barrier();
+            if (lane < NPT * nx) {                                   // x pass, item (cy, tx)
+                const int cy = div_by(lane, mx), tx = lane - cy * nx;
+                T1s[cy * NPT + tx] = interp_line(&Cs[cy * NPT], 1, fx0 + tx, bi.lag);
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane < ny * nx) {                                    // y pass, item (ty, tx)
+                const int ty = div_by(lane, mx), tx = lane - ty * nx;
+                T2[wave * 64 + lane] = interp_line(&T1s[tx], NPT, fy0 + ty, bi.lag);
+            }
+            __syncthreads();
+            if (tid < nz * ny * nx) {                                // z pass, into the tile
+                const int tz = div_by(tid, mxy), r = tid - tz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
+                tile[tidx(sz + tz, sy + ty, sx + tx)] = interp_line(&T2[r], 64, fz0 + tz, bi.lag);
+            }
         }
     } else {
         // every coarser source leaf covers a box of the padded block
@@ -336,7 +379,8 @@ __device__ __forceinline__ void commit(double* tile, double* scratch, const Bloc
             const int sx = rxl == 0 ? 0 : (rxl == 1 ? PAD : PAD + NPT), ex = rxh == 0 ? PAD : (rxh == 1 ? PAD + NPT : NP);
             const int sy = ryl == 0 ? 0 : (ryl == 1 ? PAD : PAD + NPT), ey = ryh == 0 ? PAD : (ryh == 1 ? PAD + NPT : NP);
             const int sz = rzl == 0 ? 0 : (rzl == 1 ? PAD : PAD + NPT), ez = rzh == 0 ? PAD : (rzh == 1 ? PAD + NPT : NP);
-            interp_box(tile, scratch, bi, base, id, sx, ex - sx, sy, ey - sy, sz, ez - sz, tid);
+            const double cval = ldg(base, ((uint32_t)id * BLK + tid) * 8u);
+            interp_box(tile, scratch, bi, cval, sx, ex - sx, sy, ey - sy, sz, ez - sz, tid);
         }
     }
 }
@@ -580,6 +624,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
     if (ZIN) make_plan_zipped<NPLAN, NPOINTS>(fp, bi, tid);
     else make_plan_padded<NPLAN, NPOINTS>(fp, tid);
     double pv[NPLAN];
+    double cv[CPRE];   // values of coarser face neighbours requested ahead (SYN24 first-derivative passes)
 
     auto var_base = [&](int v) -> const double* {
         return ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK;
@@ -587,7 +632,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
     auto stage = [&](int v) {   // bring variable v into tile buffer 0 (barrier before and after)
         __syncthreads();
         prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(v), tid);
-        commit<ZIN, NPLAN, PLAN_FACE>(tiles, scratch, bi, fp, pv, var_base(v), tid);
+        commit<ZIN, NPLAN, PLAN_FACE>(tiles, scratch, bi, fp, pv, cv, false, var_base(v), tid);
         __syncthreads();
     };
     auto centre = [&](int v) -> double {   // this thread's own value of variable v
@@ -649,6 +694,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
             if (t + 1 < NSTREAM) {
                 f1 = syn24_stream(t + 1);
                 prefetch<NPLAN, NEXT_USE>(pv, fp, var_base(f1), tid);
+                if (ZIN && NEXT_USE == PLAN_FACE) coarse_prefetch(cv, bi, var_base(f1), tid);
             }
             l.unext = centre((f + 11) % 24);
             l.eo = epi_prefetch<EPI>(a, nb, f, o8);
@@ -674,7 +720,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
             const double lap = fma(2.0, off, p.diag);
             stg(stash_base(10 + f), s8, lap);
             emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l.unext), l.eo);
-            commit<ZIN, NPLAN, NEXT_USE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, var_base(f1), tid);
+            commit<ZIN, NPLAN, NEXT_USE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, NEXT_USE == PLAN_FACE, var_base(f1), tid);
             if (!(OCTFD_SKIP & 128)) __syncthreads();
         };
         // pass over a variable without second derivatives (23..10)
@@ -687,7 +733,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
             const Syn24Part p = syn24_axes<false>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
             emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, l.lap, halpha, l.unext), l.eo);
             if (t + 1 < NSTREAM) {
-                commit<ZIN, NPLAN, PLAN_FACE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, var_base(f1), tid);
+                commit<ZIN, NPLAN, PLAN_FACE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, true, var_base(f1), tid);
                 if (!(OCTFD_SKIP & 128)) __syncthreads();
             }
         };
@@ -695,11 +741,11 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
         {   // pass 0: gradient of variable 10 only
             const int f = syn24_stream(0), f1 = syn24_stream(1);
             prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(f), tid);
-            commit<ZIN, NPLAN, PLAN_FACE>(tiles, scratch, bi, fp, pv, var_base(f), tid);
+            commit<ZIN, NPLAN, PLAN_FACE>(tiles, scratch, bi, fp, pv, cv, false, var_base(f), tid);
             __syncthreads();
             prefetch<NPLAN, PLAN_EDGE>(pv, fp, var_base(f1), tid);
             nx = d1_at(tiles, c, 1, ih); ny = d1_at(tiles, c, RS, ih); nz = d1_at(tiles, c, PS, ih);
-            commit<ZIN, NPLAN, PLAN_EDGE>(tiles + TILE, scratch, bi, fp, pv, var_base(f1), tid);
+            commit<ZIN, NPLAN, PLAN_EDGE>(tiles + TILE, scratch, bi, fp, pv, cv, false, var_base(f1), tid);
             __syncthreads();
         }
 #pragma unroll 1
@@ -727,7 +773,8 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, const double*
     make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);
     double pv[PLAN_FULL];
     prefetch<PLAN_FULL, PLAN_FULL>(pv, fp, zipped + v * nb * BLK, tid);
-    commit<true, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, zipped + v * nb * BLK, tid);
+    double cv[CPRE];
+    commit<true, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, zipped + v * nb * BLK, tid);
     __syncthreads();
     double* out = padded + (v * nb + b) * PBLK;
 #pragma unroll

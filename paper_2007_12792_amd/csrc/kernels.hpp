@@ -11,7 +11,7 @@ namespace octfd {
 struct DeviceTree {
     const ot_leaf* leaves;   // [nb]
     const int32_t* ghost;    // [nb][27][5]
-    const int32_t* coarse;   // [nb][8][2] distinct coarser sources and the boxes they cover
+    const int32_t* coarse;   // [nb][32] coarser sources with their boxes, and coarser faces (see HostTree)
     int64_t nb;
 };
 

@@ -165,9 +165,21 @@ int make_ghost_table(const Octree& t, const std::vector<ot_leaf>& leaves, std::v
 void make_coarse_sources(HostTree& t)
 {
     const size_t nb = t.leaves.size();
-    t.coarse.assign(nb * 16, -1);
+    t.coarse.assign(nb * kCoarseRow, -1);
     for (size_t b = 0; b < nb; ++b) {
-        int32_t* out = &t.coarse[b * 16];
+        int32_t* out = &t.coarse[b * kCoarseRow];
+        // coarser face neighbours, compacted: count, then (face, leaf id) pairs; face = 2*axis + side
+        int nf = 0;
+        for (int face = 0; face < 6; ++face) {
+            const int ax = face >> 1, step = ax == 0 ? 1 : (ax == 1 ? 3 : 9);
+            const int dir = 13 + ((face & 1) ? step : -step);
+            const int32_t* e = &t.ghost[(b * kDirs + dir) * kEntry];
+            if (e[0] != kCoarser) continue;
+            out[17 + 2 * nf] = face;
+            out[18 + 2 * nf] = e[1];
+            ++nf;
+        }
+        out[16] = nf;
         int n = 0;
         int32_t ids[8];
         int lo[8][3], hi[8][3];

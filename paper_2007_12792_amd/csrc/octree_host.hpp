@@ -10,15 +10,19 @@ namespace octfd {
 
 constexpr int kDirs = 27;          // directions (dz+1)*9 + (dy+1)*3 + (dx+1)
 constexpr int kEntry = 5;          // {kind, id0..id3}
+constexpr int kCoarseRow = 32;     // ints per block in HostTree::coarse
 enum GhostKind : int32_t { kSame = 0, kFiner = 1, kCoarser = 2 };
 
 struct HostTree {
     std::vector<ot_leaf> leaves;   // Morton order
     std::vector<int32_t> ghost;    // [nb][27][5]
-    // Derived from `ghost` for the kernels: the distinct coarser source leaves of every block, each
-    // with the box of the padded block it covers.  [nb][8][2] = {leaf id, packed ranges}, id -1
-    // ends the list; packed = xlo | xhi<<2 | ylo<<4 | yhi<<6 | zlo<<8 | zhi<<10 with 0/1/2 naming
-    // the ghost-low, interior and ghost-high part of an axis (inclusive ranges).
+    // Derived from `ghost` for the kernels, kCoarseRow ints per block:
+    //   [0..15]  the distinct coarser source leaves, each with the box of the padded block it covers:
+    //            8 x {leaf id, packed ranges}, id -1 ends the list; packed = xlo | xhi<<2 | ylo<<4 |
+    //            yhi<<6 | zlo<<8 | zhi<<10 with 0/1/2 naming the ghost-low, interior and ghost-high
+    //            part of an axis (inclusive ranges);
+    //   [16]     number of face neighbours that are coarser, then [17..28] that many {face, leaf id}
+    //            pairs, face = 2*axis + (0 low side, 1 high side).
     std::vector<int32_t> coarse;
 };
 

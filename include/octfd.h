@@ -122,7 +122,9 @@ int rhs_eval(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
 int zip(ot_tree *tree, int nvar, const double *padded_dev, double *zipped_dev, void *hip_stream);
 
 /* The three calls above fused: zipped in, zipped right-hand side out, no padded array in memory.
- * Bit-identical to zip(rhs_eval(unzip(.))). */
+ * Bit-identical to zip(rhs_eval(unzip(.))).  For SYN24 both rhs_eval and rhs_eval_zipped use
+ * variables 10..19 of the output array as scratch while they run (each is overwritten with its
+ * final value before the call's work completes). */
 int rhs_eval_zipped(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
                     const double *zipped_dev, double *rhs_zipped_dev, void *hip_stream);
 

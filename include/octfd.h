@@ -114,7 +114,19 @@ int unzip(ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev,
  *   DERIVS : (D_x u, D_y u, D_z u, Laplacian u), no dissipation
  *   WAVE   : d_t u = pi + KO(u);  d_t pi = Laplacian u + KO(pi)
  *   BURGERS: d_t u = KO(u) - u D_x u            (the paper's equation, flux along x)
- *   SYN24  : 24-field synthetic system with 72 first and 60 second derivatives. */
+ *   SYN24  : 24-field synthetic system with 72 first and 60 second derivatives.  Fields 0 = alpha,
+ *            1..3 = beta^d, 4..9 = g_xx g_xy g_xz g_yy g_yz g_zz; G_dd = 1 - g_dd/8, G_de = -g_de/8;
+ *            for s < 10:  Lap_s = fma(2, off, diag),  diag = fma(Gzz,Dzz, fma(Gyy,Dyy, Gxx*Dxx)),
+ *                         off = fma(Gyz,Dyz, fma(Gxz,Dxz, Gxy*Dxy))   of field s;
+ *            RHS_a = (((t1 + t2) + t3) - t4) + KO(u_a)  with  n = (a+1) mod 24  and
+ *              t1 = fma(beta_z, D_z u_a, fma(beta_y, D_y u_a, beta_x * D_x u_a)),
+ *              t2 = 2^-(a mod 4) * Lap_{a mod 10},
+ *              t3 = 0.25 * fma(D_z u_a, D_z u_n, fma(D_y u_a, D_y u_n, D_x u_a * D_x u_n)),
+ *              t4 = (0.5 * alpha) * u_{(a+11) mod 24}.
+ * Operator sequences (h = 2^-(l+3), d_k = u[+k]-u[-k], s_k = u[+k]+u[-k]):
+ *   D1 = (fma(45,d1, fma(-9,d2, d3)) * (1/60)) / h;
+ *   D2 = (fma(-490,u0, fma(270,s1, fma(-27,s2, 2*s3))) * (1/180)) / h^2;  Laplacian = (D2x+D2y)+D2z;
+ *   KO = sigma * (((q_x+q_y)+q_z) / (64 h)),  q = fma(-20,u0, fma(15,s1, fma(-6,s2, s3))). */
 int rhs_eval(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
              const double *padded_dev, double *rhs_padded_dev, void *hip_stream);
 

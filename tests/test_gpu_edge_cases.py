@@ -1,0 +1,114 @@
+"""More parity cases for the HIP path: uniform periodic trees (every neighbour is reached through
+the wrap), other seeds, blocks with the maximum number of coarser sources, invariants that must hold
+bit for bit, and a multi-step Burgers run against the method of characteristics."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2007_12792_amd as octfd
+import synthdata as sd
+from test_gpu_parity import assert_close, dev, dev_empty, trees  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+TP = 2.0 * np.pi
+
+
+def uniform(orc, level):
+    p = dict(lmin=level, lmax=level, pts_q20=np.zeros((1, 3), np.uint32), radius_q20=np.zeros(1, np.uint32))
+    return orc.Tree.build(**p), octfd.Tree.build(**p)
+
+
+@pytest.mark.parametrize("kind", [0, 1, 2, 3])
+def test_uniform_level3_every_kind(orc, dev, kind):  # noqa: F811
+    to, tg = uniform(orc, 3)
+    rng = np.random.default_rng(30 + kind)
+    u = rng.standard_normal((octfd.nvar_in(kind), to.n, 8, 8, 8))
+    want = to.F(kind, u, sigma=0.4)
+    out = dev_empty((octfd.nvar_out(kind), to.n, 8, 8, 8), dev)
+    tg.rhs_eval_zipped(kind, torch.from_numpy(u).to(dev), out, sigma=0.4)
+    assert_close(out.cpu().numpy(), want, "uniform L3 kind %d" % kind)
+
+
+@pytest.mark.parametrize("seed", [2, 3])
+def test_other_seeds_syn24_rk_step(orc, dev, seed):  # noqa: F811
+    to, tg = trees(orc, "T4", seed)
+    u = sd.make_fields("T4", to.leaves, seed).numpy()
+    dt = sd.time_step(5)
+    want = to.rk4_step(3, u, dt, sigma=0.4)
+    ud = torch.from_numpy(u).to(dev)
+    ws = torch.empty(tg.rk_workspace_bytes(3) // 8, dtype=torch.float64, device=dev)
+    tg.rk_step(3, ud, dt, ws, sigma=0.4)
+    assert_close(ud.cpu().numpy(), want, "T4 seed %d" % seed)
+
+
+def test_block_with_seven_coarser_sources(orc, dev):  # noqa: F811
+    # one level-3 octant refined twice around a single point: the level-5 blocks in the corners of
+    # the level-4 octet see coarser leaves on three faces, three edges and one corner
+    p = dict(lmin=3, lmax=5, pts_q20=np.array([[530000, 530000, 530000]], np.uint32), radius_q20=np.array([20000, 3000], np.uint32))
+    to, tg = orc.Tree.build(**p), octfd.Tree.build(**p)
+    g = tg.ghost_table()
+    nsrc = [len({int(g[b, d, 1]) for d in range(27) if g[b, d, 0] == 2}) for b in range(tg.n)]
+    assert max(nsrc) == 7
+    rng = np.random.default_rng(40)
+    u = rng.standard_normal((24, to.n, 8, 8, 8))
+    ud = torch.from_numpy(u).to(dev)
+    pd = dev_empty((24, to.n, 14, 14, 14), dev)
+    tg.unzip(ud, pd)
+    assert (pd.cpu().numpy() == to.unzip(u)).all()
+    out = dev_empty((24, to.n, 8, 8, 8), dev)
+    tg.rhs_eval_zipped(3, ud, out, sigma=0.4)
+    assert_close(out.cpu().numpy(), to.F(3, u, sigma=0.4), "seven coarser sources")
+
+
+def test_invariants_hold_bit_for_bit(orc, dev):  # noqa: F811
+    to, tg = trees(orc, "T3")
+    rng = np.random.default_rng(41)
+    u = torch.from_numpy(rng.standard_normal((2, to.n, 8, 8, 8))).to(dev)
+    f1, f2, f0 = (dev_empty((2, to.n, 8, 8, 8), dev) for _ in range(3))
+    tg.rhs_eval_zipped(1, u, f1, sigma=0.5)
+    tg.rhs_eval_zipped(1, 2.0 * u, f2, sigma=0.5)
+    assert torch.equal(f2, 2.0 * f1)                      # linear kind, power-of-two scaling
+    tg.rhs_eval_zipped(1, u, f0, sigma=0.0)
+    assert torch.equal(f0[0], u[1])                       # KO contributes exactly nothing
+    c = torch.full((2, to.n, 8, 8, 8), 0.75, dtype=torch.float64, device=dev)
+    c[1] = 0.0
+    ws = torch.empty(tg.rk_workspace_bytes(1) // 8, dtype=torch.float64, device=dev)
+    before = c.clone()
+    tg.rk_step(1, c, 2.0 ** -10, ws, sigma=0.4)
+    assert torch.equal(c, before)                         # a stationary state stays put
+    pd = dev_empty((2, to.n, 14, 14, 14), dev)
+    back = dev_empty((2, to.n, 8, 8, 8), dev)
+    tg.unzip(u, pd)
+    tg.zip(pd, back)
+    assert torch.equal(back, u)                           # zip(unzip(u)) == u
+
+
+def test_burgers_many_steps_towards_the_shock(orc, dev):  # noqa: F811
+    # the paper's equation and initial data with c = 1 on a uniform 128^3 lattice, integrated to
+    # t = 0.15 (the shock forms at 1/pi = 0.318): compare with the solution by characteristics
+    to, tg = uniform(orc, 4)
+    lv = to.leaves.astype(np.int64)
+    x = ((8 * lv[:, 1])[:, None, None, None] + np.arange(8)[None, None, None, :]) / 128.0
+    x = np.broadcast_to(x, (to.n, 8, 8, 8))
+    u0 = 0.5 * (1 - np.cos(TP * x))
+    dt, nsteps = 2.0 ** -9, 77
+    ud = torch.from_numpy(u0[None].copy()).to(dev)
+    ws = torch.empty(tg.rk_workspace_bytes(2) // 8, dtype=torch.float64, device=dev)
+    for _ in range(nsteps):
+        tg.rk_step(2, ud, dt, ws, sigma=0.05)
+    t = dt * nsteps
+    u = u0.copy()
+    for _ in range(200):                                  # Newton on u = u0(x - u t)
+        s = x - u * t
+        r = u - 0.5 * (1 - np.cos(TP * s))
+        u = u - r / (1 + t * 0.5 * TP * np.sin(TP * s))
+    got = ud.cpu().numpy()[0]
+    assert np.abs(got - u).max() < 2e-6
+    assert np.abs(got - u0).max() > 0.2                   # the profile has steepened a lot
+    # and the first three steps agree with the oracle to the parity tolerance
+    ud = torch.from_numpy(u0[None].copy()).to(dev)
+    ref = u0[None].copy()
+    for _ in range(3):
+        tg.rk_step(2, ud, dt, ws, sigma=0.05)
+        ref = to.rk4_step(2, ref, dt, sigma=0.05)
+    assert_close(ud.cpu().numpy(), ref, "3 Burgers steps")

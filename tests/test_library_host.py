@@ -122,3 +122,16 @@ def test_bad_arguments_are_reported_not_crashed():
     rp = octfd.RhsParams(0.4)
     assert L.rk_step(t._h, octfd.WAVE, C.byref(rp), 0.1, one, one, 16, None) == octfd.OT_E_WORKSPACE
     assert octfd.strerror(octfd.OT_E_WORKSPACE) == "workspace too small"
+
+
+def test_device_calls_report_missing_gpu_without_crashing():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("only meaningful on a machine without a GPU")
+    t = octfd.Tree.build(3, 3, np.zeros((0, 3), np.uint32), np.zeros(0, np.uint32))
+    L = octfd.lib()
+    fake = C.c_void_p(4096)
+    rp = octfd.RhsParams(0.4)
+    for rc in (L.unzip(t._h, 1, fake, fake, None), L.zip(t._h, 1, fake, fake, None),
+               L.rhs_eval_zipped(t._h, octfd.WAVE, C.byref(rp), fake, fake, None), L.octree_upload(t._h)):
+        assert rc in (octfd.OT_E_NODEVICE, octfd.OT_E_HIP)

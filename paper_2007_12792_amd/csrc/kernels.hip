@@ -89,14 +89,21 @@ __device__ __forceinline__ void stg(double* base, uint32_t byte_off, double v)
 }
 
 // Workgroups are handed to the eight XCDs (each with its own L2) round-robin by workgroup id.
-// Giving XCD x the x-th contiguous eighth of the Morton-ordered blocks keeps a block and the
-// neighbours whose data it reads on the same L2.
-constexpr int NXCD = 8;
-__device__ __forceinline__ int64_t block_of_workgroup(int64_t wg, int64_t nb)
+// Chunks of 16 Morton-consecutive blocks (two sibling octets) are dealt to the XCDs in turn: blocks
+// that run at the same time on one XCD are then close neighbours, which read each other's rows
+// through the same L2, while every XCD still sees the same mix of cheap and expensive blocks.
+// (Measured on the 102,075-block tree: 78.0 ms per step against 83.5 ms with one contiguous eighth
+// of the Morton order per XCD and 78.4 ms with no remapping.)
+constexpr int NXCD = 8, XCD_CHUNK = 16;
+__device__ __forceinline__ int64_t block_of_workgroup(int64_t wg)
 {
-    const int64_t per = (nb + NXCD - 1) / NXCD;      // blocks per XCD
-    const int64_t b = (wg % NXCD) * per + wg / NXCD;
-    return b;                                        // may be >= nb for the last XCD: caller checks
+    const int64_t x = wg % NXCD, q = wg / NXCD;
+    return (q / XCD_CHUNK) * (XCD_CHUNK * NXCD) + x * XCD_CHUNK + (q % XCD_CHUNK);   // may be >= nb: caller checks
+}
+inline unsigned grid_for_blocks(int64_t nb)
+{
+    const int64_t span = XCD_CHUNK * NXCD;
+    return (unsigned)((nb + span - 1) / span * span);
 }
 
 __device__ __forceinline__ void load_block_info(BlockInfo& bi, const DeviceTree& tr, int64_t b, int tid)
@@ -603,7 +610,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
 
     const int tid = threadIdx.x;
     const int64_t nb = tr.nb;
-    const int64_t b = block_of_workgroup(blockIdx.x, nb);
+    const int64_t b = block_of_workgroup(blockIdx.x);
     if (b >= nb) return;                             // uniform over the workgroup
     if (OCTFD_SKIP & 16) { if (tid == 0) tiles[0] = 1.0; return; }   // timing experiment: launch cost only
     load_block_info(bi, tr, b, tid);
@@ -797,8 +804,7 @@ __global__ __launch_bounds__(NTHREADS) void k_zip(int64_t nblocks, const double*
 template <int KIND, bool ZIN, int EPI>
 hipError_t launch_one(const DeviceTree& t, const RhsArgs& a, hipStream_t s)
 {
-    const int64_t per = (t.nb + NXCD - 1) / NXCD;
-    hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI>), dim3((unsigned)(per * NXCD)), dim3(NTHREADS), 0, s, t, a);
+    hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
     return hipGetLastError();
 }
 

@@ -65,6 +65,8 @@ def lib():
             f = getattr(L, name)
             f.restype = dbl
             f.argtypes = [vp, dbl]
+        L.orc_transfer.restype = i32
+        L.orc_transfer.argtypes = [vp, vp, i32, vp, vp]
         L.orc_ko_line.restype = dbl
         L.orc_ko_line.argtypes = [vp]
         L.orc_interp.restype = dbl
@@ -182,6 +184,19 @@ class Tree:
         if rc:
             raise ValueError("rk4 needs nvar_in == nvar_out")
         return z
+
+
+def transfer(src_tree, dst_tree, zipped):
+    """Zipped data on src_tree -> zipped data on dst_tree (copy / injection / interpolation from a
+    leaf one level coarser).  Raises ValueError when dst_tree is somewhere two or more levels finer."""
+    z = _f64(zipped)
+    nvar = z.shape[0]
+    assert z.shape == (nvar, src_tree.n, 8, 8, 8)
+    out = np.empty((nvar, dst_tree.n, 8, 8, 8), dtype=np.float64)
+    rc = lib().orc_transfer(src_tree._h, dst_tree._h, nvar, _p(z), _p(out))
+    if rc:
+        raise ValueError("target tree is two or more levels finer than the source tree somewhere (%d)" % rc)
+    return out
 
 
 def d1_line(u7, ih):

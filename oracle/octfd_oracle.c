@@ -26,6 +26,8 @@
  *               D1_a(D1_b u), 6th-difference Kreiss-Oliger dissipation.
  *   rhs kinds   DERIVS, WAVE, BURGERS (the paper's equation), SYN24 (24-field synthetic system).
  *   rk4         classical four-stage Runge-Kutta on zipped vectors.
+ *   transfer    after a regrid, every point of the new tree takes the old tree's value there:
+ *               copy, injection, or the same Lagrange interpolation from a one-level-coarser leaf.
  *
  * Floating point: fp64, one fixed IEEE operation sequence per formula (explicit fma() where a
  * fused multiply-add is meant; compile with -ffp-contract=off so nothing else is fused).
@@ -667,6 +669,54 @@ int orc_rk4_step(const void *tv, int kind, double sigma, double dt, double *u)
     orc_F(t, kind, sigma, st, NULL, t->n, k);                        /* k4 */
     for (size_t i = 0; i < len; i++) u[i] = fma(sixth, acc[i] + k[i], u[i]);
     free(k); free(acc); free(st);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ inter-grid transfer */
+
+/* Carry zipped data from one tree to another (the step after a regrid).  Every owned point of
+ * every leaf of the target tree, lattice point P of that leaf's level l, takes the value the
+ * source discretisation has at that place; with (l', a') the source leaf that contains it:
+ *   l' >= l   the point is node 2^(l'-l) P - 8a' of that leaf: copy it (injection when l' > l);
+ *   l' = l-1  interpolate inside that leaf exactly as for a ghost point taken from a coarser
+ *             leaf: fine coordinate f = P - 16a' per axis, even f passes through, odd f uses the
+ *             clamped six-point Lagrange row; x, then y, then z;
+ *   l' < l-1  not defined here: the function returns -8 and writes nothing.
+ * zipped_src [nvar][n_src][8^3] -> zipped_dst [nvar][n_dst][8^3]. */
+int orc_transfer(const void *srcv, const void *dstv, int nvar, const double *zipped_src, double *zipped_dst)
+{
+    const orc_tree *S = (const orc_tree *)srcv, *D = (const orc_tree *)dstv;
+    for (int64_t b = 0; b < D->n; b++) {       /* a target leaf lies inside one source leaf or covers whole ones */
+        orc_leaf B = D->leaves[b];
+        const int64_t P[3] = { NPT * (int64_t)B.ix, NPT * (int64_t)B.iy, NPT * (int64_t)B.iz };
+        int64_t L = locate(S, (int)B.level, P);
+        if (L < 0 || (int)S->leaves[L].level < (int)B.level - 1) return -8;
+    }
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t b = 0; b < D->n; b++) {
+        orc_leaf B = D->leaves[b];
+        int l = (int)B.level;
+        const int64_t a[3] = { B.ix, B.iy, B.iz };
+        for (int k = 0; k < NPT; k++) for (int j = 0; j < NPT; j++) for (int i = 0; i < NPT; i++) {
+            const int64_t P[3] = { NPT * a[0] + i, NPT * a[1] + j, NPT * a[2] + k };
+            int64_t L = locate(S, l, P);
+            orc_leaf Q = S->leaves[L];
+            const int64_t sa[3] = { Q.ix, Q.iy, Q.iz };
+            int dl = (int)Q.level - l;
+            for (int v = 0; v < nvar; v++) {
+                const double *src = zipped_src + ((size_t)v * S->n + L) * BLK;
+                double val;
+                if (dl >= 0) {
+                    int q[3]; for (int d = 0; d < 3; d++) q[d] = (int)((P[d] << dl) - NPT * sa[d]);
+                    val = src[(q[2] * NPT + q[1]) * NPT + q[0]];
+                } else {
+                    int f[3]; for (int d = 0; d < 3; d++) f[d] = (int)(P[d] - 2 * NPT * sa[d]);
+                    val = interp_xyz(src, f[0], f[1], f[2]);
+                }
+                zipped_dst[((size_t)v * D->n + b) * BLK + (k * NPT + j) * NPT + i] = val;
+            }
+        }
+    }
     return 0;
 }
 

@@ -70,13 +70,14 @@ def normal_noise(seed, numel, device="cpu", chunk=1 << 24):
 
 
 # ------------------------------------------------------------------ seed points, radii
-def seed_points(style, seed):
-    """Two refinement centres on the 2^20 lattice, (2,3) uint32."""
+def seed_points(style, seed, phase=0.0):
+    """Two refinement centres on the 2^20 lattice, (2,3) uint32.  `phase` (radians) advances the
+    "orbit" pair along its circle: the moved centres of a later regrid."""
     r = SplitMix64(seed)
     if style == "rand":      # each coordinate in [1/4, 3/4)
         pts = [[(1 << 18) + (r.next() % (1 << 19)) for _ in range(3)] for _ in range(2)]
     elif style == "orbit":   # two points opposite each other on a circle of radius 0.15
-        phi = 2.0 * math.pi * (r.next() / 2.0 ** 64)
+        phi = 2.0 * math.pi * (r.next() / 2.0 ** 64) + phase
         pts = []
         for sgn in (+1.0, -1.0):
             p = (0.5 + sgn * 0.15 * math.cos(phi), 0.5 + sgn * 0.15 * math.sin(phi), 0.5 + 2.0 ** -20)
@@ -109,9 +110,9 @@ KO_SIGMA = 0.4
 CFL = 0.25
 
 
-def tree_params(name, seed=1):
+def tree_params(name, seed=1, phase=0.0):
     c = CONFIGS[name]
-    return dict(lmin=c["lmin"], lmax=c["lmax"], pts_q20=seed_points(c["style"], seed),
+    return dict(lmin=c["lmin"], lmax=c["lmax"], pts_q20=seed_points(c["style"], seed, phase),
                 radius_q20=np.asarray(c["radius_q20"], dtype=np.uint32))
 
 

@@ -149,6 +149,34 @@ int rk_workspace_bytes(const ot_tree *tree, ot_rhs_kind kind, size_t *bytes);
 int rk_step(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,
             double *u_zipped_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/* Regrid: the tree that follows the moved refinement centres is built with octree_build; a
+ * transfer plan then carries zipped data from the old tree to the new one.  (The paper has no
+ * adaptive mesh; this is the step that surrounds the time loop in any adaptive run.)
+ *
+ * regrid_plan (host only) relates every leaf of `to` to the leaves of `from`.  The plan keeps
+ * copies of what it needs, so both trees may be freed while it lives.  Fails with
+ * OT_E_UNSUPPORTED when some leaf of `to` is two or more levels finer than the leaf of `from` that
+ * contains it (refine one level per regrid).
+ *
+ * regrid_table copies the plan to host array out[cap] of int32, cap >= 4 * (blocks of `to`):
+ * per target leaf {kind, first source leaf, number of source leaves, child octant} with kind
+ *   0  the same leaf exists in `from`: copy its block;
+ *   1  the source leaf is one level coarser: the target leaf is its child octant
+ *      (ox | oy<<1 | oz<<2) and every point is interpolated inside the source leaf exactly as a
+ *      ghost point is in unzip (fine coordinate f = 8*o + i per axis; x, then y, then z);
+ *   2  the target leaf is tiled by that many consecutive finer source leaves: point I of level l
+ *      is node 2^(l'-l) I of the level-l' source leaf that contains it, and is copied (injection).
+ *
+ * regrid_transfer: from_zipped_dev [nvar][blocks of from][8^3] -> to_zipped_dev [nvar][blocks of
+ * to][8^3] on the current device, asynchronously on hip_stream; the first call copies the plan's
+ * tables to the device, synchronously.  The arrays must not overlap. */
+typedef struct ot_transfer ot_transfer;
+int regrid_plan(const ot_tree *from, const ot_tree *to, ot_transfer **out);
+int regrid_table(const ot_transfer *plan, int32_t *out, size_t cap);
+int regrid_transfer(ot_transfer *plan, int nvar, const double *from_zipped_dev, double *to_zipped_dev,
+                    void *hip_stream);
+int regrid_free(ot_transfer *plan); /* NULL is allowed */
+
 const char *ot_strerror(int status);
 int ot_last_hip_error(void);
 

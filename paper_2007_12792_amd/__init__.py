@@ -20,6 +20,7 @@ OT_E_WORKSPACE, OT_E_HIP, OT_E_NODEVICE, OT_E_UNSUPPORTED = -5, -6, -7, -8
 EXPORTS = ["octree_build", "octree_from_leaves", "octree_num_blocks", "octree_get_leaves",
            "octree_get_ghost_table", "octree_upload", "octree_free", "ot_rhs_nvar_in", "ot_rhs_nvar_out",
            "unzip", "rhs_eval", "zip", "rhs_eval_zipped", "rk_workspace_bytes", "rk_step",
+           "regrid_plan", "regrid_table", "regrid_transfer", "regrid_free",
            "ot_strerror", "ot_last_hip_error"]
 
 
@@ -68,6 +69,10 @@ def lib():
         "rhs_eval_zipped": [vp, i32, C.POINTER(RhsParams), vp, vp, vp],
         "rk_workspace_bytes": [vp, i32, C.POINTER(sz)],
         "rk_step": [vp, i32, C.POINTER(RhsParams), dbl, vp, vp, sz, vp],
+        "regrid_plan": [vp, vp, C.POINTER(vp)],
+        "regrid_table": [vp, vp, sz],
+        "regrid_transfer": [vp, i32, vp, vp, vp],
+        "regrid_free": [vp],
         "ot_last_hip_error": [],
     }
     for name, args in sig.items():
@@ -201,3 +206,35 @@ class Tree:
         nbytes = workspace.numel() * workspace.element_size()
         _check(lib().rk_step(self._h, kind, C.byref(p), float(dt), _ptr(u), _ptr(workspace), nbytes, _stream(stream)),
                "rk_step")
+
+
+class Transfer:
+    """Handle on an ot_transfer: carries zipped data from `src` (old tree) to `dst` (regridded tree)."""
+
+    def __init__(self, src, dst):
+        h = C.c_void_p()
+        _check(lib().regrid_plan(src._h, dst._h, C.byref(h)), "regrid_plan")
+        self._h = h
+        self.n_from, self.n_to = src.n, dst.n
+
+    def __del__(self):
+        try:
+            if self._h:
+                lib().regrid_free(self._h)
+                self._h = None
+        except Exception:
+            pass
+
+    @property
+    def table(self):
+        """(n_to, 4) int32 rows {kind, first source leaf, number of source leaves, child octant}"""
+        out = np.empty((self.n_to, 4), dtype=np.int32)
+        _check(lib().regrid_table(self._h, out.ctypes.data_as(C.c_void_p), out.size), "regrid_table")
+        return out
+
+    def apply(self, zipped_from, zipped_to, stream=None):
+        nvar = zipped_from.shape[0]
+        assert tuple(zipped_from.shape) == (nvar, self.n_from, 8, 8, 8)
+        assert tuple(zipped_to.shape) == (nvar, self.n_to, 8, 8, 8)
+        _check(lib().regrid_transfer(self._h, nvar, _ptr(zipped_from), _ptr(zipped_to), _stream(stream)),
+               "regrid_transfer")

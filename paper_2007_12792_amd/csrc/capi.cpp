@@ -8,6 +8,7 @@
 #include "kernels.hpp"
 #include "octfd.h"
 #include "octree_host.hpp"
+#include "transfer.hpp"
 
 using namespace octfd;
 
@@ -17,6 +18,13 @@ struct ot_tree {
     int32_t* d_ghost = nullptr;
     int32_t* d_coarse = nullptr;
     int device = -1;   // device the tables live on, -1 = not uploaded
+};
+
+struct ot_transfer {
+    HostTransfer host;
+    char* d_base = nullptr;   // one allocation: table, source leaves, source keys, target leaves
+    DeviceTransfer dev{};
+    int device = -1;
 };
 
 namespace {
@@ -59,6 +67,38 @@ int ensure_device(ot_tree* t)
     t->d_ghost = reinterpret_cast<int32_t*>(base + og);
     t->d_coarse = reinterpret_cast<int32_t*>(base + oc);
     t->device = dev;
+    return OT_OK;
+}
+
+int ensure_device(ot_transfer* p)
+{
+    if (p->device >= 0) return OT_OK;
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (ndev <= 0) return OT_E_NODEVICE;
+    int dev = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e);
+    const HostTransfer& h = p->host;
+    auto up = [](size_t n) { return (n + 255) / 256 * 256; };
+    const size_t nt = h.table.size() * sizeof(int32_t), nf = h.from.size() * sizeof(ot_leaf);
+    const size_t nk = h.from_keys.size() * sizeof(uint64_t), no = h.to.size() * sizeof(ot_leaf);
+    const size_t of = up(nt), ok = of + up(nf), oo = ok + up(nk);
+    char* base = nullptr;
+    if ((e = hipMalloc(reinterpret_cast<void**>(&base), oo + no)) != hipSuccess) return hip_fail(e);
+    e = hipMemcpy(base, h.table.data(), nt, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(base + of, h.from.data(), nf, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(base + ok, h.from_keys.data(), nk, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(base + oo, h.to.data(), no, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(base);
+        return hip_fail(e);
+    }
+    p->d_base = base;
+    p->dev = DeviceTransfer{reinterpret_cast<const int32_t*>(base), reinterpret_cast<const ot_leaf*>(base + of),
+                            reinterpret_cast<const uint64_t*>(base + ok), reinterpret_cast<const ot_leaf*>(base + oo),
+                            static_cast<int64_t>(h.from.size()), static_cast<int64_t>(h.to.size())};
+    p->device = dev;
     return OT_OK;
 }
 
@@ -235,6 +275,46 @@ int rk_step(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double
         if (e != hipSuccess) return hip_fail(e);
     }
     return OT_OK;
+}
+
+int regrid_plan(const ot_tree* from, const ot_tree* to, ot_transfer** out)
+{
+    if (!from || !to || !out) return OT_E_BADARG;
+    *out = nullptr;
+    ot_transfer* p = new (std::nothrow) ot_transfer;
+    if (!p) return OT_E_NOMEM;
+    int rc;
+    try { rc = make_transfer(from->host.leaves, to->host.leaves, p->host); } catch (const std::bad_alloc&) { rc = OT_E_NOMEM; }
+    if (rc != OT_OK) { delete p; return rc; }
+    *out = p;
+    return OT_OK;
+}
+
+int regrid_table(const ot_transfer* plan, int32_t* out, size_t cap)
+{
+    if (!plan || !out || cap < plan->host.table.size()) return OT_E_BADARG;
+    for (size_t i = 0; i < plan->host.table.size(); ++i) out[i] = plan->host.table[i];
+    return OT_OK;
+}
+
+int regrid_transfer(ot_transfer* plan, int nvar, const double* from_zipped_dev, double* to_zipped_dev, void* hip_stream)
+{
+    if (!plan || nvar <= 0 || !from_zipped_dev || !to_zipped_dev) return OT_E_BADARG;
+    if (int rc = ensure_device(plan)) return rc;
+    hipError_t e = launch_transfer(plan->dev, nvar, from_zipped_dev, to_zipped_dev, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OT_OK : hip_fail(e);
+}
+
+int regrid_free(ot_transfer* plan)
+{
+    if (!plan) return OT_OK;
+    int rc = OT_OK;
+    if (plan->device >= 0) {
+        hipError_t e = hipFree(plan->d_base);
+        if (e != hipSuccess) rc = hip_fail(e);
+    }
+    delete plan;
+    return rc;
 }
 
 const char* ot_strerror(int status)

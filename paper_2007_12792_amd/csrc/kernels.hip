@@ -15,6 +15,7 @@
 // Arithmetic follows one fixed IEEE sequence per formula (see octfd.h); the file is compiled with
 // -ffp-contract=off, so a fused multiply-add happens exactly where fma() is written.
 #include "kernels.hpp"
+#include "lagrange.hpp"
 
 #include <type_traits>
 
@@ -43,15 +44,6 @@ constexpr int YPS = NPT * RS + 8;        // plane stride of the D1_y array, 120 
 constexpr int WY = NPT * YPS;            // D1_y u on [8 k][8 j][14 ii]
 constexpr int T1N = 64 * NP, T2N = NPT * NP * NP;            // interpolation staging
 constexpr int SCRATCH = (WZ + WY) > (T1N + T2N) ? (WZ + WY) : (T1N + T2N);   // the coarse leaf C overlays T2
-
-// six-point Lagrange weights on nodes 0..5 at r = 1/2, 3/2, ..., 11/2 (numerators over 256)
-__constant__ double c_lag[36] = {
-    63.0 / 256,  315.0 / 256, -210.0 / 256, 126.0 / 256,  -45.0 / 256,   7.0 / 256,
-    -7.0 / 256,  105.0 / 256,  210.0 / 256, -70.0 / 256,   21.0 / 256,  -3.0 / 256,
-     3.0 / 256,  -25.0 / 256,  150.0 / 256, 150.0 / 256,  -25.0 / 256,   3.0 / 256,
-    -3.0 / 256,   21.0 / 256,  -70.0 / 256, 210.0 / 256,  105.0 / 256,  -7.0 / 256,
-     7.0 / 256,  -45.0 / 256,  126.0 / 256, -210.0 / 256, 315.0 / 256,  63.0 / 256,
-   -63.0 / 256,  385.0 / 256, -990.0 / 256, 1386.0 / 256, -1155.0 / 256, 693.0 / 256};
 
 struct BlockInfo {       // per-workgroup copy of the block's table rows
     int32_t gt[27 * 5];
@@ -233,24 +225,6 @@ __device__ __forceinline__ void make_plan_padded(FillPlan<NPLAN>& fp, int tid)
         fp.src[m * NTHREADS + tid] = ok ? (uint32_t)((kk * NP + jj) * NP + ii) * 8u : 0u;
         fp.set_dst(m, ok ? tidx(kk, jj, ii) : DUMMY);
     }
-}
-
-// 1-D interpolation inside a coarse leaf: v[0..7] (stride st) are its nodes, f in [0,16) the fine
-// coordinate.  Even f passes through; odd f uses the clamped six-node stencil.
-__device__ __forceinline__ double interp_line(const double* v, int st, int f, const double* lag)
-{
-    if (!(f & 1)) return v[(f >> 1) * st];
-    const int c0 = (f - 1) >> 1;
-    const int s = min(max(c0 - 2, 0), 2);
-    const double* w = lag + (c0 - s) * 6;
-    const double* p = v + s * st;
-    double acc = w[0] * p[0];
-    acc = fma(w[1], p[st], acc);
-    acc = fma(w[2], p[2 * st], acc);
-    acc = fma(w[3], p[3 * st], acc);
-    acc = fma(w[4], p[4 * st], acc);
-    acc = fma(w[5], p[5 * st], acc);
-    return acc;
 }
 
 // q / d for the few divisors that occur here (3, 8, 11, 14 and their pairwise products), q < 65536

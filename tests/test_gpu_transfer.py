@@ -1,0 +1,83 @@
+"""Parity of the inter-grid transfer kernel (through the C ABI) against the CPU oracle, element by
+element.  The copied and injected values must be bit-identical; the interpolated ones follow the
+same IEEE operation sequence on both sides, so they are normally bit-identical too
+(bound: |gpu - oracle| <= 1e-12 |oracle| + 1e-13)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2007_12792_amd as octfd
+import synthdata as sd
+
+pytestmark = pytest.mark.gpu
+RTOL, ATOL = 1e-12, 1e-13
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    return torch.device("cuda:0")
+
+
+def both(orc, params):
+    return orc.Tree.build(**params), octfd.Tree.build(**params)
+
+
+def check(orc, dev, pa, pb, nvar, what, seed=0):
+    oa, ga = both(orc, pa)
+    ob, gb = both(orc, pb)
+    assert (oa.leaves == ga.leaves).all() and (ob.leaves == gb.leaves).all()
+    u = np.random.default_rng(seed).standard_normal((nvar, oa.n, 8, 8, 8))
+    want = orc.transfer(oa, ob, u)
+    plan = octfd.Transfer(ga, gb)
+    tab = plan.table
+    got = torch.full((nvar, gb.n, 8, 8, 8), float("nan"), dtype=torch.float64, device=dev)
+    plan.apply(torch.from_numpy(u).to(dev), got)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    exact = tab[:, 0] != 1
+    nz = int((got != want).sum())
+    print("%s: %d -> %d blocks, kinds %s, %d of %d values differ" % (what, oa.n, ob.n, np.bincount(tab[:, 0], minlength=3), nz, got.size), flush=True)
+    assert np.isfinite(got).all()
+    assert (got[:, exact] == want[:, exact]).all()
+    assert (np.abs(got - want) <= RTOL * np.abs(want) + ATOL).all()
+    return tab
+
+
+def test_orbit_regrid_small(orc, dev):
+    tab = check(orc, dev, sd.tree_params("T4", 1), sd.tree_params("T4", 1, phase=0.35), 3, "T4 phase 0.35")
+    assert all((tab[:, 0] == k).any() for k in (0, 1, 2))
+
+
+def test_identity_and_tiny_move(orc, dev):
+    check(orc, dev, sd.tree_params("T4", 1), sd.tree_params("T4", 1), 2, "T4 identity")
+    check(orc, dev, sd.tree_params("T2", 1), sd.tree_params("T2", 1, phase=0.0) | {"pts_q20": sd.seed_points("rand", 1) + np.uint32(3000)}, 1, "T2 shifted centres")
+
+
+def test_deep_injection_and_pure_prolongation(orc, dev):
+    fine = dict(lmin=3, lmax=7, pts_q20=np.array([[300000, 500000, 700000]], np.uint32), radius_q20=np.array([30000] * 4, np.uint32))
+    uni3 = dict(lmin=3, lmax=3, pts_q20=np.zeros((1, 3), np.uint32), radius_q20=np.zeros(0, np.uint32))
+    uni4 = dict(lmin=4, lmax=4, pts_q20=np.zeros((1, 3), np.uint32), radius_q20=np.zeros(0, np.uint32))
+    tab = check(orc, dev, fine, uni3, 2, "levels 3-7 -> uniform 3 (injection through up to 4 levels)")
+    assert (tab[:, 2] > 512).any()                     # some target block gathers from more than 8^3 leaves
+    tab = check(orc, dev, uni3, uni4, 2, "uniform 3 -> uniform 4 (every block interpolated)")
+    assert (tab[:, 0] == 1).all() and sorted(np.unique(tab[:, 3])) == list(range(8))
+    check(orc, dev, uni4, uni3, 1, "uniform 4 -> uniform 3")
+
+
+def test_regrid_of_the_largest_tree(orc, dev):
+    # the moved centres of a realistic regrid of the 102,075-block tree: the pair has advanced by
+    # about one finest block width along its orbit; every element is compared
+    tab = check(orc, dev, sd.tree_params("C5", 1), sd.tree_params("C5", 1, phase=0.013), 2, "C5 phase 0.013")
+    assert all((tab[:, 0] == k).sum() > 100 for k in (0, 1, 2))
+    with pytest.raises(octfd.OctfdError) as e:         # a jump of the centres that needs two levels at once
+        octfd.Transfer(octfd.Tree.build(**sd.tree_params("C4", 1)), octfd.Tree.build(**sd.tree_params("C4", 2)))
+    assert e.value.status == octfd.OT_E_UNSUPPORTED
+
+
+def test_refused_plan_leaves_no_device_work(dev):
+    coarse = octfd.Tree.build(3, 3, np.zeros((1, 3), np.uint32), np.zeros(1, np.uint32))
+    fine = octfd.Tree.build(3, 5, np.array([[1 << 19] * 3], np.uint32), np.array([60000, 40000], np.uint32))
+    with pytest.raises(octfd.OctfdError):
+        octfd.Transfer(coarse, fine)

@@ -135,3 +135,61 @@ def test_device_calls_report_missing_gpu_without_crashing():
     for rc in (L.unzip(t._h, 1, fake, fake, None), L.zip(t._h, 1, fake, fake, None),
                L.rhs_eval_zipped(t._h, octfd.WAVE, C.byref(rp), fake, fake, None), L.octree_upload(t._h)):
         assert rc in (octfd.OT_E_NODEVICE, octfd.OT_E_HIP)
+
+
+# ---------------------------------------------------------------- regrid plan (host only)
+def _containing_source(src_leaves, leaf):
+    """brute force: index of the source leaf that contains the first point of `leaf`, and all source
+    leaves inside `leaf` (independent of the library's merge walk)"""
+    s = src_leaves.astype(np.int64)
+    l, ix, iy, iz = (int(v) for v in leaf)
+    down = np.maximum(l - s[:, 0], 0)
+    up = np.maximum(s[:, 0] - l, 0)
+    holds = (((ix >> down) << up) == s[:, 1]) & (((iy >> down) << up) == s[:, 2]) & (((iz >> down) << up) == s[:, 3])
+    sh = np.maximum(s[:, 0] - l, 0)
+    within = (s[:, 0] > l) & ((s[:, 1] >> sh) == ix) & ((s[:, 2] >> sh) == iy) & ((s[:, 3] >> sh) == iz)
+    return np.nonzero(holds)[0], np.nonzero(within)[0]
+
+
+@pytest.mark.parametrize("name,phase", [("T4", 0.35), ("T4", 0.05), ("C4", 0.0)])
+def test_regrid_plan_matches_brute_force(name, phase):
+    a = octfd.Tree.build(**sd.tree_params(name, 1))
+    b = octfd.Tree.build(**sd.tree_params(name, 1, phase=phase)) if phase else octfd.Tree.build(**sd.tree_params(name, 2))
+    la, lb = a.leaves, b.leaves
+    try:
+        tab = octfd.Transfer(a, b).table
+    except octfd.OctfdError as e:
+        # a far jump of the centres may ask for a two-level refinement: then brute force must agree
+        assert e.status == octfd.OT_E_UNSUPPORTED
+        assert any(la[_containing_source(la, lf)[0][0], 0] < lf[0] - 1 for lf in lb)
+        return
+    assert tab.shape == (b.n, 4)
+    step = max(1, b.n // 400)
+    for j in list(range(0, b.n, step)) + list(np.nonzero(tab[:, 0] != 0)[0][:200]):
+        holds, within = _containing_source(la, lb[j])
+        kind, first, count, octant = (int(v) for v in tab[j])
+        if within.size:
+            assert kind == 2 and first == within[0] and count == within.size and (np.diff(within) == 1).all()
+        else:
+            assert holds.size == 1 and first == holds[0] and count == 1
+            dl = int(la[first, 0]) - int(lb[j, 0])
+            assert dl in (0, -1) and kind == (0 if dl == 0 else 1)
+            if kind == 1:
+                assert octant == (lb[j, 1] & 1) | ((lb[j, 2] & 1) << 1) | ((lb[j, 3] & 1) << 2)
+                assert tuple(lb[j, 1:] >> 1) == tuple(la[first, 1:])
+    assert set(np.unique(tab[:, 0])) <= {0, 1, 2}
+
+
+def test_regrid_plan_refuses_two_level_refinement_and_bad_arguments():
+    coarse = octfd.Tree.build(3, 3, np.zeros((1, 3), np.uint32), np.zeros(1, np.uint32))
+    fine = octfd.Tree.build(3, 5, np.array([[1 << 19] * 3], np.uint32), np.array([60000, 40000], np.uint32))
+    with pytest.raises(octfd.OctfdError) as e:
+        octfd.Transfer(coarse, fine)
+    assert e.value.status == octfd.OT_E_UNSUPPORTED
+    t = octfd.Transfer(fine, coarse)                  # coarsening by any number of levels is fine
+    assert (t.table[:, 0] != 1).all() and (t.table[:, 0] == 2).any()
+    L = octfd.lib()
+    h = C.c_void_p()
+    assert L.regrid_plan(None, coarse._h, C.byref(h)) == octfd.OT_E_BADARG
+    assert L.regrid_transfer(None, 1, None, None, None) == octfd.OT_E_BADARG
+    assert L.regrid_free(None) == octfd.OT_OK

@@ -65,6 +65,8 @@ def lib():
             f = getattr(L, name)
             f.restype = dbl
             f.argtypes = [vp, dbl]
+        L.orc_unzip_centred.restype = None
+        L.orc_unzip_centred.argtypes = [vp, i32, vp, vp]
         L.orc_transfer.restype = i32
         L.orc_transfer.argtypes = [vp, vp, i32, vp, vp]
         L.orc_ko_line.restype = dbl
@@ -145,6 +147,15 @@ class Tree:
         b, nsel, bp = self._sel(blocks)
         out = np.empty((nvar, nsel, 14, 14, 14), dtype=np.float64)
         lib().orc_unzip(self._h, nvar, _p(z), _p(out), bp, nsel)
+        return out
+
+    def unzip_centred(self, zipped):
+        """ghost rule with centred coarse-lattice stencils (coarsest level first); all blocks"""
+        z = _f64(zipped)
+        nvar = z.shape[0]
+        assert z.shape == (nvar, self.n, 8, 8, 8)
+        out = np.full((nvar, self.n, 14, 14, 14), np.nan, dtype=np.float64)
+        lib().orc_unzip_centred(self._h, nvar, _p(z), _p(out))
         return out
 
     def levels(self, blocks=None):

@@ -426,6 +426,88 @@ void orc_unzip(const void *tv, int nvar, const double *zipped, double *padded, c
     }
 }
 
+/* ------------------------------------------------------------------ unzip, centred variant */
+
+/* Variant of the ghost rule for a point whose containing leaf L is one level coarser: instead of
+ * the clamped stencil on L's own 8 nodes, every odd fine coordinate f uses the CENTRED six-point
+ * stencil on the coarse lattice, nodes c0-2 .. c0+3 with c0 = (f-1)/2, weights
+ * (3, -25, 150, 150, -25, 3)/256.  Nodes outside L's own range 0..7 are ghost points of L, so the
+ * values come from L's PADDED block (local index c+3), which must have been filled before: blocks
+ * are processed coarsest level first.  Even coordinates pass through; x, then y, then z; the same
+ * acc = w0*v0, acc = fma(w_m, v_m, acc) chain.  Copies and injections are as in orc_unzip. */
+static double cen_chain(const double v[6])
+{
+    double acc = (LAG256[2][0] / 256.0) * v[0];
+    for (int m = 1; m < 6; m++) acc = fma(LAG256[2][m] / 256.0, v[m], acc);
+    return acc;
+}
+/* pad = L's padded block (14^3); c* are L-local coarse indices in [-3, 10] */
+static double cen_x(const double *pad, int fx, int cy, int cz)
+{
+    const double *row = pad + ((size_t)(cz + PAD) * NP + (cy + PAD)) * NP + PAD;
+    if (!(fx & 1)) return row[fx / 2];
+    int c0 = (fx - 1) / 2; double v[6];
+    for (int m = 0; m < 6; m++) v[m] = row[c0 - 2 + m];
+    return cen_chain(v);
+}
+static double cen_xy(const double *pad, int fx, int fy, int cz)
+{
+    if (!(fy & 1)) return cen_x(pad, fx, fy / 2, cz);
+    int c0 = (fy - 1) / 2; double v[6];
+    for (int m = 0; m < 6; m++) v[m] = cen_x(pad, fx, c0 - 2 + m, cz);
+    return cen_chain(v);
+}
+static double cen_xyz(const double *pad, int fx, int fy, int fz)
+{
+    if (!(fz & 1)) return cen_xy(pad, fx, fy, fz / 2);
+    int c0 = (fz - 1) / 2; double v[6];
+    for (int m = 0; m < 6; m++) v[m] = cen_xy(pad, fx, fy, c0 - 2 + m);
+    return cen_chain(v);
+}
+
+/* zipped [nvar][n][8^3] -> padded [nvar][n][14^3], all blocks (a block needs the padded blocks of
+ * coarser leaves, so there is no selection). */
+void orc_unzip_centred(const void *tv, int nvar, const double *zipped, double *padded)
+{
+    const orc_tree *t = (const orc_tree *)tv;
+    for (int lev = 0; lev <= MAXLEVEL; lev++) {
+#pragma omp parallel for schedule(dynamic)
+        for (int64_t b = 0; b < t->n; b++) {
+            orc_leaf B = t->leaves[b];
+            if ((int)B.level != lev) continue;
+            int64_t N = (int64_t)NPT << lev;
+            const int64_t a[3] = { B.ix, B.iy, B.iz };
+            for (int kk = 0; kk < NP; kk++) for (int jj = 0; jj < NP; jj++) for (int ii = 0; ii < NP; ii++) {
+                const int pp[3] = { ii, jj, kk };
+                int64_t P[3];
+                for (int d = 0; d < 3; d++) P[d] = ((NPT * a[d] + pp[d] - PAD) % N + N) % N;
+                int64_t L = locate(t, lev, P);
+                orc_leaf S = t->leaves[L];
+                const int64_t sa[3] = { S.ix, S.iy, S.iz };
+                int dl = (int)S.level - lev;
+                size_t po = ((size_t)kk * NP + jj) * NP + ii;
+                for (int v = 0; v < nvar; v++) {
+                    const double *src = zipped + ((size_t)v * t->n + L) * BLK;
+                    double val;
+                    if (dl == 0) {
+                        int q[3]; for (int d = 0; d < 3; d++) q[d] = (int)(P[d] - NPT * sa[d]);
+                        val = src[(q[2] * NPT + q[1]) * NPT + q[0]];
+                    } else if (dl == 1) {
+                        int q[3]; for (int d = 0; d < 3; d++) q[d] = (int)(2 * P[d] - NPT * sa[d]);
+                        val = src[(q[2] * NPT + q[1]) * NPT + q[0]];
+                    } else if (dl == -1) {
+                        int f[3]; for (int d = 0; d < 3; d++) f[d] = (int)(P[d] - 2 * NPT * sa[d]);
+                        val = cen_xyz(padded + ((size_t)v * t->n + L) * PBLK, f[0], f[1], f[2]);
+                    } else {
+                        val = NAN;
+                    }
+                    padded[((size_t)v * t->n + b) * PBLK + po] = val;
+                }
+            }
+        }
+    }
+}
+
 /* padded [nvar][nsel][14^3] -> zipped [nvar][nsel][8^3]: strip the ghost layers */
 void orc_zip(int nvar, int64_t nsel, const double *padded, double *zipped)
 {

@@ -149,6 +149,23 @@ int rk_workspace_bytes(const ot_tree *tree, ot_rhs_kind kind, size_t *bytes);
 int rk_step(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,
             double *u_zipped_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/* Variant of the ghost rule with centred interpolation stencils (level-ordered).  Identical to
+ * unzip except for padded points whose containing leaf L is one level coarser: there every odd
+ * fine coordinate f = P - 16a' uses the centred six-point stencil on the coarse lattice, nodes
+ * c0-2 .. c0+3 with c0 = (f-1)/2 and weights (3, -25, 150, 150, -25, 3)/256, instead of the stencil
+ * clamped to L's own eight nodes.  Nodes outside 0..7 are ghost points of L and are taken from L's
+ * padded block (local index c+3), so blocks are filled coarsest level first (one launch per
+ * level) and the result depends on more than one source leaf.  Same axis order and fma chain.
+ * The interpolation error at a level jump is much smaller (no half-cell extrapolation), at the
+ * price of a padded array in memory: this rule cannot be fused into the right-hand-side kernel.
+ *
+ * rk_step_centred is rk_step with F = zip(rhs_eval(unzip_centred(.))); its workspace holds three
+ * zipped state vectors followed by one padded one (rk_centred_workspace_bytes). */
+int unzip_centred(ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev, void *hip_stream);
+int rk_centred_workspace_bytes(const ot_tree *tree, ot_rhs_kind kind, size_t *bytes);
+int rk_step_centred(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,
+                    double *u_zipped_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
 /* Regrid: the tree that follows the moved refinement centres is built with octree_build; a
  * transfer plan then carries zipped data from the old tree to the new one.  (The paper has no
  * adaptive mesh; this is the step that surrounds the time loop in any adaptive run.)

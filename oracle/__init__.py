@@ -67,6 +67,10 @@ def lib():
             f.argtypes = [vp, dbl]
         L.orc_unzip_centred.restype = None
         L.orc_unzip_centred.argtypes = [vp, i32, vp, vp]
+        L.orc_F_centred.restype = None
+        L.orc_F_centred.argtypes = [vp, i32, dbl, vp, vp]
+        L.orc_rk4_step_centred.restype = i32
+        L.orc_rk4_step_centred.argtypes = [vp, i32, dbl, dbl, vp]
         L.orc_transfer.restype = i32
         L.orc_transfer.argtypes = [vp, vp, i32, vp, vp]
         L.orc_ko_line.restype = dbl
@@ -187,6 +191,21 @@ class Tree:
         out = np.empty((NVAR_OUT[kind], nsel, 8, 8, 8), dtype=np.float64)
         lib().orc_F(self._h, kind, float(sigma), _p(z), bp, nsel, _p(out))
         return out
+
+    def F_centred(self, kind, zipped, sigma=0.0):
+        z = _f64(zipped)
+        assert z.shape == (NVAR_IN[kind], self.n, 8, 8, 8)
+        out = np.empty((NVAR_OUT[kind], self.n, 8, 8, 8), dtype=np.float64)
+        lib().orc_F_centred(self._h, kind, float(sigma), _p(z), _p(out))
+        return out
+
+    def rk4_step_centred(self, kind, u, dt, sigma=0.0):
+        z = _f64(u).copy()
+        assert z.shape == (NVAR_IN[kind], self.n, 8, 8, 8)
+        rc = lib().orc_rk4_step_centred(self._h, kind, float(sigma), float(dt), _p(z))
+        if rc:
+            raise ValueError("rk4 needs nvar_in == nvar_out")
+        return z
 
     def rk4_step(self, kind, u, dt, sigma=0.0):
         z = _f64(u).copy()

@@ -20,6 +20,7 @@ OT_E_WORKSPACE, OT_E_HIP, OT_E_NODEVICE, OT_E_UNSUPPORTED = -5, -6, -7, -8
 EXPORTS = ["octree_build", "octree_from_leaves", "octree_num_blocks", "octree_get_leaves",
            "octree_get_ghost_table", "octree_upload", "octree_free", "ot_rhs_nvar_in", "ot_rhs_nvar_out",
            "unzip", "rhs_eval", "zip", "rhs_eval_zipped", "rk_workspace_bytes", "rk_step",
+           "unzip_centred", "rk_centred_workspace_bytes", "rk_step_centred",
            "regrid_plan", "regrid_table", "regrid_transfer", "regrid_free",
            "ot_strerror", "ot_last_hip_error"]
 
@@ -69,6 +70,9 @@ def lib():
         "rhs_eval_zipped": [vp, i32, C.POINTER(RhsParams), vp, vp, vp],
         "rk_workspace_bytes": [vp, i32, C.POINTER(sz)],
         "rk_step": [vp, i32, C.POINTER(RhsParams), dbl, vp, vp, sz, vp],
+        "unzip_centred": [vp, i32, vp, vp, vp],
+        "rk_centred_workspace_bytes": [vp, i32, C.POINTER(sz)],
+        "rk_step_centred": [vp, i32, C.POINTER(RhsParams), dbl, vp, vp, sz, vp],
         "regrid_plan": [vp, vp, C.POINTER(vp)],
         "regrid_table": [vp, vp, sz],
         "regrid_transfer": [vp, i32, vp, vp, vp],
@@ -177,6 +181,11 @@ class Tree:
         assert tuple(zipped.shape) == (nvar, self.n, 8, 8, 8) and tuple(padded.shape) == (nvar, self.n, 14, 14, 14)
         _check(lib().unzip(self._h, nvar, _ptr(zipped), _ptr(padded), _stream(stream)), "unzip")
 
+    def unzip_centred(self, zipped, padded, stream=None):
+        nvar = zipped.shape[0]
+        assert tuple(zipped.shape) == (nvar, self.n, 8, 8, 8) and tuple(padded.shape) == (nvar, self.n, 14, 14, 14)
+        _check(lib().unzip_centred(self._h, nvar, _ptr(zipped), _ptr(padded), _stream(stream)), "unzip_centred")
+
     def zip(self, padded, zipped, stream=None):
         nvar = padded.shape[0]
         assert tuple(zipped.shape) == (nvar, self.n, 8, 8, 8) and tuple(padded.shape) == (nvar, self.n, 14, 14, 14)
@@ -206,6 +215,18 @@ class Tree:
         nbytes = workspace.numel() * workspace.element_size()
         _check(lib().rk_step(self._h, kind, C.byref(p), float(dt), _ptr(u), _ptr(workspace), nbytes, _stream(stream)),
                "rk_step")
+
+    def rk_centred_workspace_bytes(self, kind):
+        n = C.c_size_t()
+        _check(lib().rk_centred_workspace_bytes(self._h, kind, C.byref(n)), "rk_centred_workspace_bytes")
+        return n.value
+
+    def rk_step_centred(self, kind, u, dt, workspace, sigma=0.0, stream=None):
+        assert tuple(u.shape) == (nvar_in(kind), self.n, 8, 8, 8)
+        p = RhsParams(float(sigma))
+        nbytes = workspace.numel() * workspace.element_size()
+        _check(lib().rk_step_centred(self._h, kind, C.byref(p), float(dt), _ptr(u), _ptr(workspace), nbytes,
+                                     _stream(stream)), "rk_step_centred")
 
 
 class Transfer:

@@ -17,6 +17,7 @@ struct ot_tree {
     ot_leaf* d_leaves = nullptr;
     int32_t* d_ghost = nullptr;
     int32_t* d_coarse = nullptr;
+    int32_t* d_by_level = nullptr;
     int device = -1;   // device the tables live on, -1 = not uploaded
 };
 
@@ -51,14 +52,15 @@ int ensure_device(ot_tree* t)
     // kernels address one variable's zipped array with 32-bit byte offsets
     if (t->host.leaves.size() >= (size_t(1) << 20)) return OT_E_UNSUPPORTED;
     const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
-    const size_t nc = t->host.coarse.size() * sizeof(int32_t);
-    // one allocation for the three tables, each part 256-byte aligned
-    const size_t ol = 0, og = (nl + 255) / 256 * 256, oc = og + (ng + 255) / 256 * 256;
+    const size_t nc = t->host.coarse.size() * sizeof(int32_t), nv = t->host.by_level.size() * sizeof(int32_t);
+    // one allocation for the four tables, each part 256-byte aligned
+    const size_t ol = 0, og = (nl + 255) / 256 * 256, oc = og + (ng + 255) / 256 * 256, ov = oc + (nc + 255) / 256 * 256;
     char* base = nullptr;
-    if ((e = hipMalloc(reinterpret_cast<void**>(&base), oc + nc)) != hipSuccess) return hip_fail(e);
+    if ((e = hipMalloc(reinterpret_cast<void**>(&base), ov + nv)) != hipSuccess) return hip_fail(e);
     e = hipMemcpy(base + ol, t->host.leaves.data(), nl, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(base + og, t->host.ghost.data(), ng, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(base + oc, t->host.coarse.data(), nc, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(base + ov, t->host.by_level.data(), nv, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         (void)hipFree(base);
         return hip_fail(e);
@@ -66,6 +68,7 @@ int ensure_device(ot_tree* t)
     t->d_leaves = reinterpret_cast<ot_leaf*>(base + ol);
     t->d_ghost = reinterpret_cast<int32_t*>(base + og);
     t->d_coarse = reinterpret_cast<int32_t*>(base + oc);
+    t->d_by_level = reinterpret_cast<int32_t*>(base + ov);
     t->device = dev;
     return OT_OK;
 }
@@ -104,7 +107,7 @@ int ensure_device(ot_transfer* p)
 
 DeviceTree dev_view(const ot_tree* t)
 {
-    return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, static_cast<int64_t>(t->host.leaves.size())};
+    return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, t->d_by_level, static_cast<int64_t>(t->host.leaves.size())};
 }
 
 bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }
@@ -209,6 +212,15 @@ int unzip(ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev,
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
+int unzip_centred(ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
+{
+    if (!tree || nvar <= 0 || nvar > 65535 || !zipped_dev || !padded_dev) return OT_E_BADARG;
+    if (int rc = ensure_device(tree)) return rc;
+    hipError_t e = launch_unzip_centred(dev_view(tree), tree->host.level_start, nvar, zipped_dev, padded_dev,
+                                        static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OT_OK : hip_fail(e);
+}
+
 int zip(ot_tree* tree, int nvar, const double* padded_dev, double* zipped_dev, void* hip_stream)
 {
     if (!tree || nvar <= 0 || !zipped_dev || !padded_dev) return OT_E_BADARG;
@@ -272,6 +284,50 @@ int rk_step(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double
     const Epilogue ep[4] = {kRkFirst, kRkMiddle, kRkMiddle, kRkLast};
     for (int i = 0; i < 4; ++i) {
         hipError_t e = launch_rhs(dv, kind, true, ep[i], st[i], s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return OT_OK;
+}
+
+int rk_centred_workspace_bytes(const ot_tree* tree, ot_rhs_kind kind, size_t* bytes)
+{
+    size_t zipped3 = 0;
+    if (int rc = rk_workspace_bytes(tree, kind, &zipped3)) return rc;
+    *bytes = zipped3 + static_cast<size_t>(ot_rhs_nvar_in(kind)) * tree->host.leaves.size() * 2744 * sizeof(double);
+    return OT_OK;
+}
+
+int rk_step_centred(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u_zipped_dev,
+                    void* workspace_dev, size_t workspace_bytes, void* hip_stream)
+{
+    if (!tree || !kind_ok(kind) || !params || !u_zipped_dev || !workspace_dev) return OT_E_BADARG;
+    size_t need = 0, zipped3 = 0;
+    if (int rc = rk_centred_workspace_bytes(tree, kind, &need)) return rc;
+    if (int rc = rk_workspace_bytes(tree, kind, &zipped3)) return rc;
+    if (workspace_bytes < need) return OT_E_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % 256) return OT_E_BADARG;
+    if (int rc = ensure_device(tree)) return rc;
+    const size_t len = zipped3 / (3 * sizeof(double));
+    const int nvar = ot_rhs_nvar_in(kind);
+    double* acc = static_cast<double*>(workspace_dev);
+    double* sa = acc + len;
+    double* sb = sa + len;
+    double* pad = sb + len;                     // ghost-padded copy of the current stage vector
+    double* u = u_zipped_dev;
+    const DeviceTree dv = dev_view(tree);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const double sg = params->ko_sigma;
+    // the padded copy decouples a stage's input from its output, so one stage vector would do; the
+    // two are kept so that the SYN24 scratch of the last stage (sb) never aliases its input
+    const double* stage_in[4] = {u, sa, sb, sa};
+    const RhsArgs st[4] = {{pad, sa, acc, u, sa, 0.5 * dt, sg},
+                           {pad, sb, acc, u, sb, 0.5 * dt, sg},
+                           {pad, sa, acc, u, sa, dt, sg},
+                           {pad, nullptr, acc, u, sb, dt / 6.0, sg}};
+    const Epilogue ep[4] = {kRkFirst, kRkMiddle, kRkMiddle, kRkLast};
+    for (int i = 0; i < 4; ++i) {
+        hipError_t e = launch_unzip_centred(dv, tree->host.level_start, nvar, stage_in[i], pad, s);
+        if (e == hipSuccess) e = launch_rhs(dv, kind, false, ep[i], st[i], s);
         if (e != hipSuccess) return hip_fail(e);
     }
     return OT_OK;

@@ -265,6 +265,61 @@ __device__ __forceinline__ void interp_box(double* tile, double* scratch, const 
     }
 }
 
+// The same for the centred variant of the ghost rule: the source is the coarser leaf's PADDED block
+// (cpad, 14^3, filled by an earlier launch), every odd fine coordinate f takes the centred stencil
+// on coarse nodes c0-2 .. c0+3, c0 = f >> 1, which may reach into that leaf's ghost layers.
+// The box needs coarse nodes clo .. chi per axis, at most 13 of them.
+constexpr int CBOX = 13;
+constexpr int CT1 = CBOX * CBOX * NP, CT2 = CBOX * NP * NP;      // staging after the x pass / the y pass
+__device__ __forceinline__ double centred_line(const double* v, int st, int f, int clo, const double* lag)
+{
+    const int c0 = f >> 1;
+    if (!(f & 1)) return v[(c0 - clo) * st];
+    const double* w = lag + 12;                                  // the centred row, r = 5/2
+    const double* p = v + (c0 - 2 - clo) * st;
+    double acc = w[0] * p[0];
+    acc = fma(w[1], p[st], acc);
+    acc = fma(w[2], p[2 * st], acc);
+    acc = fma(w[3], p[3 * st], acc);
+    acc = fma(w[4], p[4 * st], acc);
+    acc = fma(w[5], p[5 * st], acc);
+    return acc;
+}
+__device__ __forceinline__ void interp_box_centred(double* tile, double* scratch, const BlockInfo& bi, const double* cpad,
+                                                   int sx, int nx, int sy, int ny, int sz, int nz, int tid)
+{
+    double* T1 = scratch;            // after the x pass  [cz][cy][tx]
+    double* T2 = T1 + CT1;           // after the y pass  [cz][ty][tx]
+    double* C = T2;                  // the coarse sub-box [cz][cy][cx]: dead once the x pass is done
+    const int fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
+    const int fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
+    const int fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
+    const int clx = (fx0 >> 1) - 2, ncx = ((fx0 + nx - 1) >> 1) + 3 - clx + 1;
+    const int cly = (fy0 >> 1) - 2, ncy = ((fy0 + ny - 1) >> 1) + 3 - cly + 1;
+    const int clz = (fz0 >> 1) - 2, ncz = ((fz0 + nz - 1) >> 1) + 3 - clz + 1;
+    const uint32_t mcx = div_magic(ncx), mcxy = div_magic(ncx * ncy), mx = div_magic(nx), mxy = div_magic(nx * ny);
+    __syncthreads();                 // everybody is done with the staging arrays
+    for (int q = tid; q < ncz * ncy * ncx; q += NTHREADS) {
+        const int cz = div_by(q, mcxy), r = q - cz * ncx * ncy, cy = div_by(r, mcx), cx = r - cy * ncx;
+        C[q] = cpad[((clz + cz + PAD) * NP + (cly + cy + PAD)) * NP + (clx + cx + PAD)];
+    }
+    __syncthreads();
+    for (int q = tid; q < ncz * ncy * nx; q += NTHREADS) {       // x pass, item (row = cz*ncy + cy, tx)
+        const int row = div_by(q, mx), tx = q - row * nx;
+        T1[q] = centred_line(&C[row * ncx], 1, fx0 + tx, clx, bi.lag);
+    }
+    __syncthreads();
+    for (int q = tid; q < ncz * ny * nx; q += NTHREADS) {        // y pass, item (cz, ty, tx)
+        const int cz = div_by(q, mxy), r = q - cz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
+        T2[q] = centred_line(&T1[cz * ncy * nx + tx], nx, fy0 + ty, cly, bi.lag);
+    }
+    __syncthreads();
+    for (int q = tid; q < nz * ny * nx; q += NTHREADS) {         // z pass, into the tile
+        const int tz = div_by(q, mxy), r = q - tz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
+        tile[tidx(sz + tz, sy + ty, sx + tx)] = centred_line(&T2[r], nx * ny, fz0 + tz, clz, bi.lag);
+    }
+}
+
 // Filling the tile of one variable is split in two so that the global loads of the next variable
 // can be in flight while the current one is being differentiated:
 //   prefetch(): issue the planned loads into registers;
@@ -766,6 +821,48 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, const double*
     }
 }
 
+// Level-ordered ghost fill, centred variant: launched once per level, coarsest first; `blocks` lists
+// the blocks of that level.  Copies and injections as in k_unzip; boxes that come from a coarser
+// leaf are interpolated from that leaf's padded block, which an earlier launch has written.
+__global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const int32_t* __restrict__ blocks,
+                                                            const double* __restrict__ zipped, double* padded)
+{
+    __shared__ double tile[TILE];
+    __shared__ double scratch[CT1 + CT2];
+    __shared__ BlockInfo bi;
+    __shared__ uint32_t plan_src[PLAN_FULL * NTHREADS];
+    const int tid = threadIdx.x;
+    const int64_t b = blocks[blockIdx.x], v = blockIdx.y, nb = tr.nb;
+    load_block_info(bi, tr, b, tid);
+    __syncthreads();
+    FillPlan<PLAN_FULL> fp;
+    fp.src = plan_src;
+    make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);
+    double pv[PLAN_FULL];
+    prefetch<PLAN_FULL, PLAN_FULL>(pv, fp, zipped + v * nb * BLK, tid);
+    double cv[CPRE];
+    commit<false, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, zipped, tid);   // stores only
+#pragma unroll 1
+    for (int sidx = 0; sidx < 8; ++sidx) {
+        const int32_t id = bi.cs[2 * sidx];
+        if (id < 0) break;
+        const int pk = bi.cs[2 * sidx + 1];
+        const int rxl = pk & 3, rxh = (pk >> 2) & 3, ryl = (pk >> 4) & 3, ryh = (pk >> 6) & 3, rzl = (pk >> 8) & 3, rzh = (pk >> 10) & 3;
+        const int sx = rxl == 0 ? 0 : (rxl == 1 ? PAD : PAD + NPT), ex = rxh == 0 ? PAD : (rxh == 1 ? PAD + NPT : NP);
+        const int sy = ryl == 0 ? 0 : (ryl == 1 ? PAD : PAD + NPT), ey = ryh == 0 ? PAD : (ryh == 1 ? PAD + NPT : NP);
+        const int sz = rzl == 0 ? 0 : (rzl == 1 ? PAD : PAD + NPT), ez = rzh == 0 ? PAD : (rzh == 1 ? PAD + NPT : NP);
+        interp_box_centred(tile, scratch, bi, padded + (v * nb + id) * PBLK, sx, ex - sx, sy, ey - sy, sz, ez - sz, tid);
+    }
+    __syncthreads();
+    double* out = padded + (v * nb + b) * PBLK;
+#pragma unroll
+    for (int m = 0; m < PLAN_FULL; ++m) {
+        const int p = tid + m * NTHREADS;
+        const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
+        if (p < PBLK) out[p] = tile[tidx(kk, jj, ii)];
+    }
+}
+
 __global__ __launch_bounds__(NTHREADS) void k_zip(int64_t nblocks, const double* __restrict__ padded, double* __restrict__ zipped)
 {
     const int tid = threadIdx.x;
@@ -785,7 +882,16 @@ hipError_t launch_one(const DeviceTree& t, const RhsArgs& a, hipStream_t s)
 template <int KIND>
 hipError_t launch_kind(const DeviceTree& t, bool zin, Epilogue ep, const RhsArgs& a, hipStream_t s)
 {
-    if (!zin) return ep == kOutPadded ? launch_one<KIND, false, kOutPadded>(t, a, s) : hipErrorInvalidValue;
+    if (!zin) {
+        switch (ep) {
+        case kOutPadded: return launch_one<KIND, false, kOutPadded>(t, a, s);
+        case kOutZipped: return launch_one<KIND, false, kOutZipped>(t, a, s);
+        case kRkFirst: return launch_one<KIND, false, kRkFirst>(t, a, s);
+        case kRkMiddle: return launch_one<KIND, false, kRkMiddle>(t, a, s);
+        case kRkLast: return launch_one<KIND, false, kRkLast>(t, a, s);
+        default: return hipErrorInvalidValue;
+        }
+    }
     switch (ep) {
     case kOutZipped: return launch_one<KIND, true, kOutZipped>(t, a, s);
     case kRkFirst: return launch_one<KIND, true, kRkFirst>(t, a, s);
@@ -802,6 +908,21 @@ hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, dou
     if (t.nb <= 0 || nvar <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_unzip, dim3((unsigned)t.nb, (unsigned)nvar), dim3(NTHREADS), 0, s, t, zipped, padded);
     return hipGetLastError();
+}
+
+hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, int nvar, const double* zipped,
+                                double* padded, hipStream_t s)
+{
+    if (t.nb <= 0 || nvar <= 0) return hipSuccess;
+    for (int l = 0; l < 20; ++l) {                   // coarsest level first; the stream orders the launches
+        const int64_t n = level_start[l + 1] - level_start[l];
+        if (n <= 0) continue;
+        hipLaunchKernelGGL(k_unzip_centred, dim3((unsigned)n, (unsigned)nvar), dim3(NTHREADS), 0, s, t,
+                           t.by_level + level_start[l], zipped, padded);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, double* zipped, hipStream_t s)

@@ -12,6 +12,7 @@ struct DeviceTree {
     const ot_leaf* leaves;   // [nb]
     const int32_t* ghost;    // [nb][27][5]
     const int32_t* coarse;   // [nb][32] coarser sources with their boxes, and coarser faces (see HostTree)
+    const int32_t* by_level; // [nb] block ids sorted by level
     int64_t nb;
 };
 
@@ -36,8 +37,11 @@ struct RhsArgs {
 };
 
 hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, double* padded, hipStream_t s);
+// level-ordered ghost fill with centred coarse-lattice stencils; level_start[21] as in HostTree
+hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, int nvar, const double* zipped,
+                                double* padded, hipStream_t s);
 hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, double* zipped, hipStream_t s);
-// in_zipped = false: args.in is padded (then ep must be kOutPadded); true: args.in is zipped
+// in_zipped = false: args.in is padded; true: args.in is zipped
 hipError_t launch_rhs(const DeviceTree& t, ot_rhs_kind kind, bool in_zipped, Epilogue ep, const RhsArgs& args,
                       hipStream_t s);
 

@@ -208,6 +208,17 @@ void make_coarse_sources(HostTree& t)
     }
 }
 
+void make_level_lists(HostTree& t)
+{
+    const size_t nb = t.leaves.size();
+    int64_t count[21] = {};
+    for (size_t b = 0; b < nb; ++b) ++count[t.leaves[b].level + 1];
+    for (int l = 1; l <= 20; ++l) count[l] += count[l - 1];       // count[l] = first slot of level l
+    for (int l = 0; l <= 20; ++l) t.level_start[l] = count[l];
+    t.by_level.assign(nb, 0);
+    for (size_t b = 0; b < nb; ++b) t.by_level[count[t.leaves[b].level]++] = static_cast<int32_t>(b);
+}
+
 int build_tree(const ot_build_params& p, HostTree& out)
 {
     if (p.lmin < 3 || p.lmax < p.lmin || p.lmax > 19) return OT_E_BADARG;
@@ -234,7 +245,7 @@ int build_tree(const ot_build_params& p, HostTree& out)
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
     const int rc = make_ghost_table(t, out.leaves, out.ghost);
-    if (rc == OT_OK) make_coarse_sources(out);
+    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); }
     return rc;
 }
 
@@ -261,7 +272,7 @@ int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out)
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
     const int rc = make_ghost_table(t, out.leaves, out.ghost);
-    if (rc == OT_OK) make_coarse_sources(out);
+    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); }
     return rc;
 }
 

@@ -24,11 +24,16 @@ struct HostTree {
     //   [16]     number of face neighbours that are coarser, then [17..28] that many {face, leaf id}
     //            pairs, face = 2*axis + (0 low side, 1 high side).
     std::vector<int32_t> coarse;
+    // Block ids sorted by level (ascending, Morton order within a level): blocks of level l are
+    // by_level[level_start[l] .. level_start[l+1]).  Used by the level-ordered ghost fill.
+    std::vector<int32_t> by_level;
+    int64_t level_start[21] = {};
 };
 
 // Each returns an OT_* status.
 int build_tree(const ot_build_params& p, HostTree& out);
 int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out);
 void make_coarse_sources(HostTree& t);
+void make_level_lists(HostTree& t);
 
 }  // namespace octfd

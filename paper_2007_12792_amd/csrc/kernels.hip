@@ -42,8 +42,19 @@ constexpr int TILE = NP * PS;            // 14 planes
 constexpr int WZ = NPT * PS;             // D1_z u on [8 k][14 jj][14 ii]
 constexpr int YPS = NPT * RS + 8;        // plane stride of the D1_y array, 120 = 24 (mod 32)
 constexpr int WY = NPT * YPS;            // D1_y u on [8 k][8 j][14 ii]
-constexpr int T1N = 64 * NP, T2N = NPT * NP * NP;            // interpolation staging
-constexpr int SCRATCH = (WZ + WY) > (T1N + T2N) ? (WZ + WY) : (T1N + T2N);   // the coarse leaf C overlays T2
+// wy and wz together need 2,560 doubles; the ghost interpolation stages several coarser leaves at
+// once in the same area and profits from the 448 more that still let two workgroups share a CU
+constexpr int SCRATCH = WZ + WY + 448;
+
+constexpr int ROUND_SRC = 4;                 // source leaves per round (one register each while in flight)
+struct BoxPlan {
+    int32_t nround;
+    int32_t rbeg[9];                         // round r covers sources rbeg[r] .. rbeg[r+1]-1
+    int32_t n1[8], n2[8], n3[8], bstart[8];  // per round: items of the x / y / z pass, start of region B
+    int32_t o1[8], o2[8], o3[8];             // per source: offset of its items inside its round's pass
+    uint32_t mx[8], mpl[8];                  // per source: magic numbers for dividing by nx and by nx*ny
+    int16_t sx[8], nx[8], sy[8], ny[8], sz[8], nz[8], fx0[8], fy0[8], fz0[8];
+};
 
 struct BlockInfo {       // per-workgroup copy of the block's table rows
     int32_t gt[27 * 5];
@@ -51,6 +62,7 @@ struct BlockInfo {       // per-workgroup copy of the block's table rows
                          // list; [16] number of coarser faces, [17..28] {face, leaf id} pairs
     uint32_t level, ax, ay, az;
     double lag[36];
+    BoxPlan box;         // filled by make_box_plan()
 };
 
 __device__ __forceinline__ int tidx(int kk, int jj, int ii) { return kk * PS + jj * RS + ii; }
@@ -227,41 +239,104 @@ __device__ __forceinline__ void make_plan_padded(FillPlan<NPLAN>& fp, int tid)
     }
 }
 
+
+// Interpolation of the boxes of the padded block that come from coarser leaves (every such leaf
+// covers one box; a coarser leaf spans 16 fine points per axis and never contains the block itself,
+// so a box is 3 or 11 points wide per axis and at least one axis is 3 wide).
+// The x, y and z passes run over the boxes of SEVERAL source leaves at once ("round"), their work
+// items packed densely over the 512 threads: four workgroup barriers per round instead of per
+// source, and all source leaves of a round are requested from memory together.
+// Staging per round: region A holds the coarse leaves (512 each) and, after the x pass, the y-pass
+// results; region B, behind it, holds the x-pass results.
 // q / d for the few divisors that occur here (3, 8, 11, 14 and their pairwise products), q < 65536
 __device__ __forceinline__ uint32_t div_magic(uint32_t d) { return 0xffffffffu / d + 1u; }
 __device__ __forceinline__ int div_by(int q, uint32_t magic) { return (int)__umulhi((uint32_t)q, magic); }
-
-// Interpolate one box [sx,sx+nx) x [sy,sy+ny) x [sz,sz+nz) of the tile from a coarser leaf:
-// x pass, y pass, z pass through LDS staging.  Uniform control flow; starts with a barrier (the
-// staging arrays may still be in use) and ends without one.
-// cval = this thread's element (index tid) of the coarse leaf's 8^3 values.
-__device__ __forceinline__ void interp_box(double* tile, double* scratch, const BlockInfo& bi, double cval,
-                                           int sx, int nx, int sy, int ny, int sz, int nz, int tid)
+// done by one thread per block, once: boxes from the packed region ranges, greedy rounds in list order
+__device__ void make_box_plan(BlockInfo& bi)
 {
-    double* T1 = scratch;            // after the x pass  [cz][cy][tx], row stride NP
-    double* T2 = T1 + T1N;           // after the y pass  [cz][ty][tx]
-    double* C = T2;                  // the coarse leaf, 8^3: dead once the x pass is done
-    const uint32_t mx = div_magic(nx), mxy = div_magic(nx * ny);
-    // fine coordinate of the box's first point inside the coarse leaf (aligned to 16 points)
-    const int fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
-    const int fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
-    const int fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
-    __syncthreads();                 // everybody is done with the staging arrays (C overlays T2)
-    C[tid] = cval;
-    __syncthreads();
-    for (int q = tid; q < 64 * nx; q += NTHREADS) {              // x pass
-        const int row = div_by(q, mx), tx = q - row * nx;        // row = cz*8 + cy
-        T1[row * NP + tx] = interp_line(&C[row * NPT], 1, fx0 + tx, bi.lag);
+    BoxPlan& bp = bi.box;
+    int nr = 0, sumc = 0, sum1 = 0, sum2 = 0, sum3 = 0, ns = 0;
+    bp.rbeg[0] = 0;
+    for (int s = 0; s < 8; ++s) {
+        if (bi.cs[2 * s] < 0) break;
+        const int pk = bi.cs[2 * s + 1];
+        const int rxl = pk & 3, rxh = (pk >> 2) & 3, ryl = (pk >> 4) & 3, ryh = (pk >> 6) & 3, rzl = (pk >> 8) & 3, rzh = (pk >> 10) & 3;
+        const int sx = rxl == 0 ? 0 : (rxl == 1 ? PAD : PAD + NPT), ex = rxh == 0 ? PAD : (rxh == 1 ? PAD + NPT : NP);
+        const int sy = ryl == 0 ? 0 : (ryl == 1 ? PAD : PAD + NPT), ey = ryh == 0 ? PAD : (ryh == 1 ? PAD + NPT : NP);
+        const int sz = rzl == 0 ? 0 : (rzl == 1 ? PAD : PAD + NPT), ez = rzh == 0 ? PAD : (rzh == 1 ? PAD + NPT : NP);
+        const int nx = ex - sx, ny = ey - sy, nz = ez - sz;
+        const int t1 = 64 * nx, t2 = NPT * ny * nx, t3 = nz * ny * nx;
+        // does the source still fit into the current round?
+        const int a_need = max(sumc + BLK, sum2 + t2);
+        if (s > bp.rbeg[nr] && (s - bp.rbeg[nr] == ROUND_SRC || a_need + sum1 + t1 > SCRATCH)) {
+            bp.n1[nr] = sum1; bp.n2[nr] = sum2; bp.n3[nr] = sum3; bp.bstart[nr] = max(sumc, sum2);
+            ++nr;
+            bp.rbeg[nr] = s;
+            sumc = sum1 = sum2 = sum3 = 0;
+        }
+        bp.o1[s] = sum1; bp.o2[s] = sum2; bp.o3[s] = sum3;
+        sumc += BLK; sum1 += t1; sum2 += t2; sum3 += t3;
+        bp.mx[s] = div_magic(nx); bp.mpl[s] = div_magic(nx * ny);
+        bp.sx[s] = sx; bp.nx[s] = nx; bp.sy[s] = sy; bp.ny[s] = ny; bp.sz[s] = sz; bp.nz[s] = nz;
+        // fine coordinate of the box's first point inside the coarse leaf (aligned to 16 points)
+        bp.fx0[s] = (NPT * bi.ax + sx + 16 - PAD) & 15;
+        bp.fy0[s] = (NPT * bi.ay + sy + 16 - PAD) & 15;
+        bp.fz0[s] = (NPT * bi.az + sz + 16 - PAD) & 15;
+        ns = s + 1;
     }
-    __syncthreads();
-    for (int q = tid; q < NPT * ny * nx; q += NTHREADS) {        // y pass
-        const int cz = div_by(q, mxy), r = q - cz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
-        T2[(cz * NP + ty) * NP + tx] = interp_line(&T1[cz * NPT * NP + tx], NP, fy0 + ty, bi.lag);
+    if (ns > 0) {
+        bp.n1[nr] = sum1; bp.n2[nr] = sum2; bp.n3[nr] = sum3; bp.bstart[nr] = max(sumc, sum2);
+        ++nr;
+        bp.rbeg[nr] = ns;
     }
-    __syncthreads();
-    for (int q = tid; q < nz * ny * nx; q += NTHREADS) {         // z pass, into the tile
-        const int tz = div_by(q, mxy), r = q - tz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
-        tile[tidx(sz + tz, sy + ty, sx + tx)] = interp_line(&T2[ty * NP + tx], NP * NP, fz0 + tz, bi.lag);
+    bp.nround = nr;
+}
+// the largest single box (11 x 11 x 3 or 3) must fit: 968 + 704
+static_assert(NPT * 121 + 64 * 11 <= SCRATCH && BLK + 64 * 11 <= SCRATCH, "interpolation staging");
+
+// Uniform control flow; starts with a barrier (the staging area may still be in use) and ends
+// without one.  base = one variable's zipped array.
+__device__ __forceinline__ void interp_boxes(double* tile, double* scratch, const BlockInfo& bi,
+                                             const double* __restrict__ base, int tid)
+{
+    const BoxPlan& bp = bi.box;
+#pragma unroll 1
+    for (int r = 0; r < bp.nround; ++r) {
+        const int s0 = bp.rbeg[r], s1 = bp.rbeg[r + 1];
+        double* A = scratch;
+        double* B = scratch + bp.bstart[r];
+        double cv[ROUND_SRC];
+#pragma unroll
+        for (int q = 0; q < ROUND_SRC; ++q)
+            if (s0 + q < s1) cv[q] = ldg(base, ((uint32_t)bi.cs[2 * (s0 + q)] * BLK + tid) * 8u);
+        __syncthreads();                         // everybody is done with the staging area
+#pragma unroll
+        for (int q = 0; q < ROUND_SRC; ++q)
+            if (s0 + q < s1) A[q * BLK + tid] = cv[q];
+        __syncthreads();
+        for (int q = tid; q < bp.n1[r]; q += NTHREADS) {             // x pass, item (source, row = cz*8 + cy, tx)
+            int s = s0;
+            while (s + 1 < s1 && q >= bp.o1[s + 1]) ++s;
+            const int local = q - bp.o1[s], nx = bp.nx[s];
+            const int row = div_by(local, bp.mx[s]), tx = local - row * nx;
+            B[q] = interp_line(&A[(s - s0) * BLK + row * NPT], 1, bp.fx0[s] + tx, bi.lag);
+        }
+        __syncthreads();
+        for (int q = tid; q < bp.n2[r]; q += NTHREADS) {             // y pass, item (source, cz, ty, tx)
+            int s = s0;
+            while (s + 1 < s1 && q >= bp.o2[s + 1]) ++s;
+            const int local = q - bp.o2[s], nx = bp.nx[s], pl = nx * bp.ny[s];
+            const int cz = div_by(local, bp.mpl[s]), rr = local - cz * pl, ty = div_by(rr, bp.mx[s]), tx = rr - ty * nx;
+            A[q] = interp_line(&B[bp.o1[s] + cz * NPT * nx + tx], nx, bp.fy0[s] + ty, bi.lag);
+        }
+        __syncthreads();
+        for (int q = tid; q < bp.n3[r]; q += NTHREADS) {             // z pass, item (source, tz, ty, tx), into the tile
+            int s = s0;
+            while (s + 1 < s1 && q >= bp.o3[s + 1]) ++s;
+            const int local = q - bp.o3[s], nx = bp.nx[s], pl = nx * bp.ny[s];
+            const int tz = div_by(local, bp.mpl[s]), rr = local - tz * pl, ty = div_by(rr, bp.mx[s]), tx = rr - ty * nx;
+            tile[tidx(bp.sz[s] + tz, bp.sy[s] + ty, bp.sx[s] + tx)] = interp_line(&A[bp.o2[s] + rr], pl, bp.fz0[s] + tz, bi.lag);
+        }
     }
 }
 
@@ -405,19 +480,7 @@ __device__ __forceinline__ void commit(double* tile, double* scratch, const Bloc
             }
         }
     } else {
-        // every coarser source leaf covers a box of the padded block
-#pragma unroll 1
-        for (int sidx = 0; sidx < 8; ++sidx) {
-            const int32_t id = bi.cs[2 * sidx];
-            if (id < 0) break;
-            const int pk = bi.cs[2 * sidx + 1];
-            const int rxl = pk & 3, rxh = (pk >> 2) & 3, ryl = (pk >> 4) & 3, ryh = (pk >> 6) & 3, rzl = (pk >> 8) & 3, rzh = (pk >> 10) & 3;
-            const int sx = rxl == 0 ? 0 : (rxl == 1 ? PAD : PAD + NPT), ex = rxh == 0 ? PAD : (rxh == 1 ? PAD + NPT : NP);
-            const int sy = ryl == 0 ? 0 : (ryl == 1 ? PAD : PAD + NPT), ey = ryh == 0 ? PAD : (ryh == 1 ? PAD + NPT : NP);
-            const int sz = rzl == 0 ? 0 : (rzl == 1 ? PAD : PAD + NPT), ez = rzh == 0 ? PAD : (rzh == 1 ? PAD + NPT : NP);
-            const double cval = ldg(base, ((uint32_t)id * BLK + tid) * 8u);
-            interp_box(tile, scratch, bi, cval, sx, ex - sx, sy, ey - sy, sz, ez - sz, tid);
-        }
+        interp_boxes(tile, scratch, bi, base, tid);
     }
 }
 
@@ -644,6 +707,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
     if (OCTFD_SKIP & 16) { if (tid == 0) tiles[0] = 1.0; return; }   // timing experiment: launch cost only
     load_block_info(bi, tr, b, tid);
     __syncthreads();
+    if (tid == 0) make_box_plan(bi);                 // read only after the next barrier
     if (OCTFD_SKIP & 32) { if (tid == 0) tiles[0] = bi.lag[3]; return; }   // timing experiment: + block info
 
     int i, j, k;
@@ -804,12 +868,14 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, const double*
     const int64_t b = blockIdx.x, v = blockIdx.y, nb = tr.nb;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
+    if (tid == 0) make_box_plan(bi);
     FillPlan<PLAN_FULL> fp;
     fp.src = plan_src;
     make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);
     double pv[PLAN_FULL];
     prefetch<PLAN_FULL, PLAN_FULL>(pv, fp, zipped + v * nb * BLK, tid);
     double cv[CPRE];
+    __syncthreads();                                 // the box plan is complete
     commit<true, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, zipped + v * nb * BLK, tid);
     __syncthreads();
     double* out = padded + (v * nb + b) * PBLK;

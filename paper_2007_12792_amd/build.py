@@ -19,11 +19,10 @@ def hipcc():
 def build(verbose=False):
     """Always recompiles.  -ffp-contract=off: a fused multiply-add is issued only where the source
     writes fma(), which is what makes results reproducible against a separately compiled reference."""
-    extra = os.environ.get("OCTFD_CXXFLAGS", "").split()
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument", "-x", "hip",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB] + extra
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)

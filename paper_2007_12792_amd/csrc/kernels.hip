@@ -30,12 +30,7 @@ constexpr int K_COARSER = 2, K_SAME = 0;
 // stride of 200 = 8 (mod 32).  A wavefront holds one j row of the block, its lanes run over
 // (i, k): the eight x-contiguous values of four consecutive k planes then fall into 32 different
 // 8-byte banks, and shifting the access by any stencil offset keeps that property.
-#ifndef OCTFD_SKIP
-#define OCTFD_SKIP 0   // timing experiments: 1 = no mixed derivatives, 2 = no global loads, 4 = no stencils, 8 = no stores
-#endif
-#ifndef OCTFD_WAVES_PER_SIMD
-#define OCTFD_WAVES_PER_SIMD 4
-#endif
+constexpr int WAVES_PER_SIMD = 4;        // 128 VGPRs per lane: two workgroups of the stage kernels share a compute unit
 constexpr int RS = NP;                   // 14
 constexpr int PS = NP * RS + 4;          // 200
 constexpr int TILE = NP * PS;            // 14 planes
@@ -411,7 +406,7 @@ __device__ __forceinline__ void prefetch(double (&v)[NPLAN], const FillPlan<NPLA
     // the last entry in use may reach beyond the face prefix: read element 0 instead
     if (USE == PLAN_FACE && NPLAN > PLAN_FACE && tid + (USE - 1) * NTHREADS >= NFACE) off[USE - 1] = 0;
 #pragma unroll
-    for (int m = 0; m < USE; ++m) v[m] = (OCTFD_SKIP & 2) ? 1.0 : ldg(base, off[m]);
+    for (int m = 0; m < USE; ++m) v[m] = ldg(base, off[m]);
 }
 
 // Values of the coarser face neighbours can be requested together with the tile data
@@ -577,7 +572,7 @@ __device__ __forceinline__ Mixed mixed_derivs(const double* tile, double* wy, do
         const int ct = tidx(lb + PAD, jj, la + PAD);
         wz[lb * PS + jj * RS + (la + PAD)] = d1_at(tile, ct, PS, ih);
     }
-    if (!(OCTFD_SKIP & 128)) __syncthreads();
+    __syncthreads();
     Mixed r;
     r.dxy = d1_at(wy, owny, 1, ih);
     __builtin_amdgcn_sched_barrier(0);
@@ -615,7 +610,6 @@ __device__ __forceinline__ void emit(const RhsArgs& a, int64_t nb, int w, int64_
         return;
     }
     const int64_t f = (int64_t)w * nb * BLK;
-    if ((OCTFD_SKIP & 8) && k != 12345.678) return;
     if (EPI == kOutZipped) {
         stg(a.out + f, o8, k);
     } else if (EPI == kRkFirst) {
@@ -647,7 +641,6 @@ __device__ __forceinline__ Syn24Part syn24_axes(const double* t, int c, double* 
     Syn24Part r;
     const double u0 = t[c];
     r.diag = 0.0;
-    if (OCTFD_SKIP & 4) { r.t1 = u0; r.t3q = nx; r.ko = ny; nx = nz + u0; return r; }
     const AxisOps x = axis_ops<WITH_D2>(t, c, 1, u0, ih, ih2);
     r.t1 = bx * x.d1;
     r.t3q = x.d1 * nx;
@@ -689,7 +682,7 @@ constexpr int NSTREAM = 25;
 __device__ __forceinline__ int syn24_stream(int t) { return t == 0 ? 10 : (t <= 10 ? 10 - t : 34 - t); }
 
 template <int KIND, bool ZIN, int EPI>
-__global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTree tr, RhsArgs a)
+__global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr, RhsArgs a)
 {
     constexpr int NBUF = KIND == OT_RHS_SYN24 ? 2 : 1;
     __shared__ double tiles[NBUF * TILE];
@@ -704,11 +697,9 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
     const int64_t nb = tr.nb;
     const int64_t b = block_of_workgroup(blockIdx.x);
     if (b >= nb) return;                             // uniform over the workgroup
-    if (OCTFD_SKIP & 16) { if (tid == 0) tiles[0] = 1.0; return; }   // timing experiment: launch cost only
     load_block_info(bi, tr, b, tid);
     __syncthreads();
     if (tid == 0) make_box_plan(bi);                 // read only after the next barrier
-    if (OCTFD_SKIP & 32) { if (tid == 0) tiles[0] = bi.lag[3]; return; }   // timing experiment: + block info
 
     int i, j, k;
     point_of(tid, i, j, k);
@@ -811,9 +802,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
             Look l{0.0, 0.0, {0.0, 0.0}};
             issue(t, f, l, f1, next_use);
             const Syn24Part p = syn24_axes<true>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
-            Mixed mx;
-            if (OCTFD_SKIP & 1) { mx.dxy = p.t1; mx.dxz = p.t3q; mx.dyz = p.ko; }
-            else mx = mixed_derivs(T, wy, wz, tid, owny, ownz, ih);
+            const Mixed mx = mixed_derivs(T, wy, wz, tid, owny, ownz, ih);
             double off = Gxy * mx.dxy;
             off = fma(Gxz, mx.dxz, off);
             off = fma(Gyz, mx.dyz, off);
@@ -821,7 +810,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
             stg(stash_base(10 + f), s8, lap);
             emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l.unext), l.eo);
             commit<ZIN, NPLAN, NEXT_USE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, NEXT_USE == PLAN_FACE, var_base(f1), tid);
-            if (!(OCTFD_SKIP & 128)) __syncthreads();
+            __syncthreads();
         };
         // pass over a variable without second derivatives (23..10)
         auto pass_light = [&](int t) {
@@ -834,7 +823,7 @@ __global__ __launch_bounds__(NTHREADS, OCTFD_WAVES_PER_SIMD) void k_rhs(DeviceTr
             emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, l.lap, halpha, l.unext), l.eo);
             if (t + 1 < NSTREAM) {
                 commit<ZIN, NPLAN, PLAN_FACE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, true, var_base(f1), tid);
-                if (!(OCTFD_SKIP & 128)) __syncthreads();
+                __syncthreads();
             }
         };
 

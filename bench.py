@@ -39,6 +39,58 @@ def measured_traffic(config, nb):
     return rec.get("bytes_per_launch")
 
 
+def other_kernels(args, cfg, kind, dev):
+    """ms per call and algorithmic GB/s of the kernels that the headline step does not use."""
+    import numpy as np
+    import torch
+
+    import paper_2007_12792_amd as octfd
+    import synthdata as sd
+
+    t = octfd.Tree.build(**sd.tree_params(args.config, args.seed))
+    nb, Vi, Vo = t.n, octfd.nvar_in(kind), octfd.nvar_out(kind)
+    u = sd.make_fields(args.config, t.leaves, args.seed, device=dev)
+    pad = torch.empty((Vi, nb, 14, 14, 14), dtype=torch.float64, device=dev)
+    rp = torch.zeros((Vo, nb, 14, 14, 14), dtype=torch.float64, device=dev)
+    out = torch.empty((Vo, nb, 8, 8, 8), dtype=torch.float64, device=dev)
+    t.upload()
+    stream = torch.cuda.current_stream()
+
+    def timed(f):
+        f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            f()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    pts = nb * 512
+    res = {}
+
+    def row(name, ms, bytes_per_call, what):
+        res[name] = {"ms": ms, "algorithmic_GBs": bytes_per_call / ms / 1e6, "bytes": what}
+
+    row("unzip", timed(lambda: t.unzip(u, pad)), 50.9 * pts * Vi, "8 B read + 42.9 B written per block-point and variable")
+    row("unzip_centred", timed(lambda: t.unzip_centred(u, pad)), 50.9 * pts * Vi, "as unzip")
+    t.unzip(u, pad)
+    row("rhs_eval", timed(lambda: t.rhs_eval(kind, pad, rp, sigma=sd.KO_SIGMA)), (42.9 * Vi + 8.0 * Vo) * pts,
+        "42.9 B read per input variable + 8 B written per output variable")
+    row("zip", timed(lambda: t.zip(rp, out)), 16.0 * pts * Vo, "8 B read + 8 B written")
+    row("rhs_eval_zipped", timed(lambda: t.rhs_eval_zipped(kind, u, out, sigma=sd.KO_SIGMA)), (8.0 * Vi + 8.0 * Vo) * pts,
+        "8 B read per input variable + 8 B written per output variable")
+    if cfg["style"] == "orbit":
+        t2 = octfd.Tree.build(**sd.tree_params(args.config, args.seed, phase=0.013))
+        plan = octfd.Transfer(t, t2)
+        u2 = torch.empty((Vi, t2.n, 8, 8, 8), dtype=torch.float64, device=dev)
+        row("regrid_transfer", timed(lambda: plan.apply(u, u2)), 16.0 * t2.n * 512 * Vi, "8 B read + 8 B written")
+        res["regrid_transfer"]["blocks_copied_interpolated_injected"] = np.bincount(plan.table[:, 0], minlength=3).tolist()
+    print(json.dumps({"workload": args.config, "n_blocks": nb, "n_vars_in": Vi, "n_vars_out": Vo, "calls_timed": args.steps,
+                      "kernels": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +100,10 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-blocks", type=int, default=0, help="0 = every block of the tree")
+    ap.add_argument("--other-kernels", action="store_true",
+                    help="instead of the benchmark, time every other kernel of the library once on the workload (the "
+                         "literal unzip / rhs_eval / zip calls, the centred ghost rule, the fused right-hand side, the "
+                         "regrid transfer) and print one JSON line; this is what the summaries under profiles/ are made with")
     ap.add_argument("--calibrate-copy", type=float, default=0.0, metavar="GB",
                     help="instead of the benchmark, run 5 plain device copies of this many GB (a kernel of known "
                          "HBM traffic, used to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -75,6 +131,9 @@ def main():
         return
     cfg = sd.CONFIGS[args.config]
     kind = octfd.KINDS[cfg["kind"]]
+    if args.other_kernels:
+        other_kernels(args, cfg, kind, dev)
+        return
     if octfd.nvar_in(kind) != octfd.nvar_out(kind):
         sys.exit("bench.py: the timed step is rk_step; choose a workload whose kind can be stepped")
     p = sd.tree_params(args.config, args.seed)

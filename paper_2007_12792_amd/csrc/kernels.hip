@@ -847,14 +847,20 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
 
 // ---------------------------------------------------------------- unzip / zip kernels
 
-__global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, const double* __restrict__ zipped, double* __restrict__ padded)
+__global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, const double* __restrict__ zipped, double* __restrict__ padded)
 {
     __shared__ double tile[TILE];
     __shared__ double scratch[SCRATCH];
     __shared__ BlockInfo bi;
     __shared__ uint32_t plan_src[PLAN_FULL * NTHREADS];
     const int tid = threadIdx.x;
-    const int64_t b = blockIdx.x, v = blockIdx.y, nb = tr.nb;
+    // Workgroup v + nvar b: with the workgroups dealt to the eight XCDs in turn, an XCD sees a fixed
+    // subset of the variables (all of them when nvar is a multiple of 8: v mod 8) for consecutive
+    // blocks one after the other, so a ghost row it fetches was, or soon will be, an interior row of
+    // a block it handles for the same variable and is served by its L2.  (Measured on the
+    // 102,075-block tree with 24 variables: 22 GB fetched per call against 77 GB with the blocks of
+    // one variable launched together.)
+    const int64_t b = blockIdx.x / nvar, v = blockIdx.x - b * nvar, nb = tr.nb;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
     if (tid == 0) make_box_plan(bi);
@@ -961,7 +967,7 @@ hipError_t launch_kind(const DeviceTree& t, bool zin, Epilogue ep, const RhsArgs
 hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, double* padded, hipStream_t s)
 {
     if (t.nb <= 0 || nvar <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_unzip, dim3((unsigned)t.nb, (unsigned)nvar), dim3(NTHREADS), 0, s, t, zipped, padded);
+    hipLaunchKernelGGL(k_unzip, dim3((unsigned)(t.nb * nvar)), dim3(NTHREADS), 0, s, t, nvar, zipped, padded);
     return hipGetLastError();
 }
 

@@ -45,7 +45,7 @@ def dev_empty(shape, dev):
     return torch.full(shape, float("nan"), dtype=torch.float64, device=dev)
 
 
-@pytest.mark.parametrize("name,nvar", [("C1", 1), ("T2", 1), ("T4", 3)])
+@pytest.mark.parametrize("name,nvar", [("C1", 1), ("T2", 1), ("T4", 3), ("T4", 8), ("T2", 13)])
 def test_unzip_and_zip(orc, dev, name, nvar):
     to, tg = trees(orc, name)
     rng = np.random.default_rng(21)

@@ -81,3 +81,25 @@ def test_refused_plan_leaves_no_device_work(dev):
     fine = octfd.Tree.build(3, 5, np.array([[1 << 19] * 3], np.uint32), np.array([60000, 40000], np.uint32))
     with pytest.raises(octfd.OctfdError):
         octfd.Transfer(coarse, fine)
+
+
+def test_step_regrid_step_matches_the_oracle(orc, dev):
+    """An adaptive run in miniature: one RK4 step of the 24-field system, a regrid to the tree of the
+    moved centres with the state carried over, one more step; the same sequence through the oracle."""
+    kind = octfd.SYN24
+    pa, pb = sd.tree_params("T4", 1), sd.tree_params("T4", 1, phase=0.2)
+    oa, ga = both(orc, pa)
+    ob, gb = both(orc, pb)
+    dt, sg = sd.time_step(5), sd.KO_SIGMA
+    u = sd.make_fields("T4", oa.leaves, 1)
+    want = orc.transfer(oa, ob, oa.rk4_step(kind, u.numpy(), dt, sg))
+    want = ob.rk4_step(kind, want, dt, sg)
+    ua = u.to(dev).clone()
+    ga.rk_step(kind, ua, dt, torch.empty(ga.rk_workspace_bytes(kind) // 8, dtype=torch.float64, device=dev), sigma=sg)
+    ub = torch.full((24, gb.n, 8, 8, 8), float("nan"), dtype=torch.float64, device=dev)
+    octfd.Transfer(ga, gb).apply(ua, ub)
+    gb.rk_step(kind, ub, dt, torch.empty(gb.rk_workspace_bytes(kind) // 8, dtype=torch.float64, device=dev), sigma=sg)
+    torch.cuda.synchronize()
+    got = ub.cpu().numpy()
+    print("step, regrid %d -> %d blocks, step: %d of %d values differ" % (oa.n, ob.n, int((got != want).sum()), got.size), flush=True)
+    assert (np.abs(got - want) <= RTOL * np.abs(want) + ATOL).all()

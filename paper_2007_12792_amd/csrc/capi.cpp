@@ -216,6 +216,7 @@ int unzip(ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev,
 int unzip_centred(ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
 {
     if (!tree || nvar <= 0 || nvar > 65535 || !zipped_dev || !padded_dev) return OT_E_BADARG;
+    if (tree->host.leaves.size() * static_cast<size_t>(nvar) > 0x7fffffffu) return OT_E_UNSUPPORTED;   // one workgroup each
     if (int rc = ensure_device(tree)) return rc;
     hipError_t e = launch_unzip_centred(dev_view(tree), tree->host.level_start, nvar, zipped_dev, padded_dev,
                                         static_cast<hipStream_t>(hip_stream));

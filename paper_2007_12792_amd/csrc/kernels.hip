@@ -885,7 +885,7 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, con
 // Level-ordered ghost fill, centred variant: launched once per level, coarsest first; `blocks` lists
 // the blocks of that level.  Copies and injections as in k_unzip; boxes that come from a coarser
 // leaf are interpolated from that leaf's padded block, which an earlier launch has written.
-__global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const int32_t* __restrict__ blocks,
+__global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const int32_t* __restrict__ blocks, int nvar,
                                                             const double* __restrict__ zipped, double* padded)
 {
     __shared__ double tile[TILE];
@@ -893,7 +893,8 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const
     __shared__ BlockInfo bi;
     __shared__ uint32_t plan_src[PLAN_FULL * NTHREADS];
     const int tid = threadIdx.x;
-    const int64_t b = blocks[blockIdx.x], v = blockIdx.y, nb = tr.nb;
+    // variable fastest in the launch order, as in k_unzip
+    const int64_t q = blockIdx.x / nvar, v = blockIdx.x - q * nvar, b = blocks[q], nb = tr.nb;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
     FillPlan<PLAN_FULL> fp;
@@ -978,8 +979,8 @@ hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start,
     for (int l = 0; l < 20; ++l) {                   // coarsest level first; the stream orders the launches
         const int64_t n = level_start[l + 1] - level_start[l];
         if (n <= 0) continue;
-        hipLaunchKernelGGL(k_unzip_centred, dim3((unsigned)n, (unsigned)nvar), dim3(NTHREADS), 0, s, t,
-                           t.by_level + level_start[l], zipped, padded);
+        hipLaunchKernelGGL(k_unzip_centred, dim3((unsigned)(n * nvar)), dim3(NTHREADS), 0, s, t,
+                           t.by_level + level_start[l], nvar, zipped, padded);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -123,8 +123,10 @@ __device__ __forceinline__ void load_block_info(BlockInfo& bi, const DeviceTree&
 //   [0, NFACE)      interior and the six face slabs: all that stencils along the axes read;
 //   [NFACE, NEDGE)  the twelve edge slabs: read in addition by the mixed second derivatives;
 //   [NEDGE, PBLK)   the eight corners: needed only when the whole padded block is written out.
-// Fetching only the prefix in use matters because every ghost row is its own cache line in the
-// neighbour's zipped storage: faces alone touch 288 lines per tile, the full tile 588.
+// Fetching only the prefix in use matters because every 8-point ghost row is a 64-byte half of a
+// 128-byte line of the neighbour's zipped storage, of which an x ghost uses three values: faces
+// alone touch 288 rows per tile (152 lines), faces and edges 516 rows (288 lines), the full tile
+// 588 rows (336 lines).
 constexpr int NFACE = BLK + 6 * PAD * NPT * NPT;                 // 1664
 constexpr int NEDGE = NFACE + 12 * PAD * PAD * NPT;              // 2528
 constexpr int PLAN_FACE = (NFACE + NTHREADS - 1) / NTHREADS;     // 4 entries per thread

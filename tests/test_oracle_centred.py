@@ -143,3 +143,25 @@ def test_error_constant_is_smaller_than_with_clamped_stencils(orc):
     e_clamped = np.abs(t.unzip(f(x, y, z)[None])[0] - f(X, Y, Z))[coarse].max()
     e_centred = np.abs(t.unzip_centred(f(x, y, z)[None])[0] - f(X, Y, Z))[coarse].max()
     assert e_centred < e_clamped / 10.0
+
+
+def test_centred_step_equals_the_clamped_step_without_level_jumps_and_tracks_a_plane_wave(orc):
+    t = uniform_tree(orc, 3)
+    x, y, z = coords(t.leaves)
+    om = 2 * np.pi * np.sqrt(2.0)
+    ph = 2 * np.pi * (x + y)
+    u = np.stack([np.sin(ph), -om * np.cos(ph)])
+    dt = sd.time_step(3)
+    a = t.rk4_step(1, u, dt, 0.1)
+    b = t.rk4_step_centred(1, u, dt, 0.1)
+    assert (a == b).all()                              # no coarser leaf anywhere: the same arithmetic
+    # on a tree with level jumps the step stays close to the exact solution
+    t2 = two_level_tree(orc)
+    x, y, z = coords(t2.leaves)
+    ph = 2 * np.pi * (x + y)
+    v = np.stack([np.sin(ph), -om * np.cos(ph)])
+    dt = sd.time_step(4)
+    for _ in range(4):
+        v = t2.rk4_step_centred(1, v, dt, 0.4)
+    exact = np.sin(ph - om * 4 * dt)
+    assert np.abs(v[0] - exact).max() < 2e-6

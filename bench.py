@@ -81,6 +81,13 @@ def other_kernels(args, cfg, kind, dev):
     row("zip", timed(lambda: t.zip(rp, out)), 16.0 * pts * Vo, "8 B read + 8 B written")
     row("rhs_eval_zipped", timed(lambda: t.rhs_eval_zipped(kind, u, out, sigma=sd.KO_SIGMA)), (8.0 * Vi + 8.0 * Vo) * pts,
         "8 B read per input variable + 8 B written per output variable")
+    if Vi == Vo:
+        ws = torch.empty(t.rk_centred_workspace_bytes(kind) // 8, dtype=torch.float64, device=dev)
+        uc = u.clone()
+        dt = sd.time_step(cfg["lmax"])
+        row("rk_step_centred", timed(lambda: t.rk_step_centred(kind, uc, dt, ws, sigma=sd.KO_SIGMA)), 4 * 34.0 * pts * Vi,
+            "whole RK4 step with the centred ghost rule; 34 B per block-point, variable and stage as for rk_step")
+        del ws, uc
     if cfg["style"] == "orbit":
         t2 = octfd.Tree.build(**sd.tree_params(args.config, args.seed, phase=0.013))
         plan = octfd.Transfer(t, t2)

@@ -156,11 +156,14 @@ int rk_step(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double
  * clamped to L's own eight nodes.  Nodes outside 0..7 are ghost points of L and are taken from L's
  * padded block (local index c+3), so blocks are filled coarsest level first (one launch per
  * level) and the result depends on more than one source leaf.  Same axis order and fma chain.
- * The interpolation error at a level jump is much smaller (no half-cell extrapolation), at the
- * price of a padded array in memory: this rule cannot be fused into the right-hand-side kernel.
+ * The interpolation error at a level jump is much smaller (no half-cell extrapolation) and level
+ * jumps stay stable for wave propagation over long times.
  *
- * rk_step_centred is rk_step with F = zip(rhs_eval(unzip_centred(.))); its workspace holds three
- * zipped state vectors followed by one padded one (rk_centred_workspace_bytes). */
+ * rk_step_centred is rk_step with F = zip(rhs_eval(unzip_centred(.))), bit-identical to that
+ * composition, but only the padded blocks of the leaves that serve as coarser sources are ever
+ * written to memory (level by level, before each stage); everything else is fused as in rk_step.
+ * Its workspace holds three zipped state vectors followed by those padded blocks
+ * (rk_centred_workspace_bytes), 256-byte aligned. */
 int unzip_centred(ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev, void *hip_stream);
 int rk_centred_workspace_bytes(const ot_tree *tree, ot_rhs_kind kind, size_t *bytes);
 int rk_step_centred(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,

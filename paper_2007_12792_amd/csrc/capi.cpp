@@ -18,6 +18,8 @@ struct ot_tree {
     int32_t* d_ghost = nullptr;
     int32_t* d_coarse = nullptr;
     int32_t* d_by_level = nullptr;
+    int32_t* d_src_slot = nullptr;
+    int32_t* d_src_by_level = nullptr;
     int device = -1;   // device the tables live on, -1 = not uploaded
 };
 
@@ -52,23 +54,28 @@ int ensure_device(ot_tree* t)
     // kernels address one variable's zipped array with 32-bit byte offsets
     if (t->host.leaves.size() >= (size_t(1) << 20)) return OT_E_UNSUPPORTED;
     const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
-    const size_t nc = t->host.coarse.size() * sizeof(int32_t), nv = t->host.by_level.size() * sizeof(int32_t);
-    // one allocation for the four tables, each part 256-byte aligned
-    const size_t ol = 0, og = (nl + 255) / 256 * 256, oc = og + (ng + 255) / 256 * 256, ov = oc + (nc + 255) / 256 * 256;
+    // one allocation for all tables, each part 256-byte aligned
+    const HostTree& h = t->host;
+    const void* part[6] = {h.leaves.data(), h.ghost.data(), h.coarse.data(), h.by_level.data(), h.src_slot.data(),
+                           h.src_by_level.data()};
+    const size_t bytes[6] = {nl, ng, h.coarse.size() * sizeof(int32_t), h.by_level.size() * sizeof(int32_t),
+                             h.src_slot.size() * sizeof(int32_t), h.src_by_level.size() * sizeof(int32_t)};
+    size_t off[7] = {0};
+    for (int i = 0; i < 6; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
     char* base = nullptr;
-    if ((e = hipMalloc(reinterpret_cast<void**>(&base), ov + nv)) != hipSuccess) return hip_fail(e);
-    e = hipMemcpy(base + ol, t->host.leaves.data(), nl, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(base + og, t->host.ghost.data(), ng, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(base + oc, t->host.coarse.data(), nc, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(base + ov, t->host.by_level.data(), nv, hipMemcpyHostToDevice);
+    if ((e = hipMalloc(reinterpret_cast<void**>(&base), off[6] + 256)) != hipSuccess) return hip_fail(e);
+    for (int i = 0; i < 6 && e == hipSuccess; ++i)
+        if (bytes[i]) e = hipMemcpy(base + off[i], part[i], bytes[i], hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         (void)hipFree(base);
         return hip_fail(e);
     }
-    t->d_leaves = reinterpret_cast<ot_leaf*>(base + ol);
-    t->d_ghost = reinterpret_cast<int32_t*>(base + og);
-    t->d_coarse = reinterpret_cast<int32_t*>(base + oc);
-    t->d_by_level = reinterpret_cast<int32_t*>(base + ov);
+    t->d_leaves = reinterpret_cast<ot_leaf*>(base + off[0]);
+    t->d_ghost = reinterpret_cast<int32_t*>(base + off[1]);
+    t->d_coarse = reinterpret_cast<int32_t*>(base + off[2]);
+    t->d_by_level = reinterpret_cast<int32_t*>(base + off[3]);
+    t->d_src_slot = reinterpret_cast<int32_t*>(base + off[4]);
+    t->d_src_by_level = reinterpret_cast<int32_t*>(base + off[5]);
     t->device = dev;
     return OT_OK;
 }
@@ -107,7 +114,8 @@ int ensure_device(ot_transfer* p)
 
 DeviceTree dev_view(const ot_tree* t)
 {
-    return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, t->d_by_level, static_cast<int64_t>(t->host.leaves.size())};
+    return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, t->d_by_level, static_cast<int64_t>(t->host.leaves.size()),
+                      t->d_src_slot, t->d_src_by_level, static_cast<int64_t>(t->host.src_by_level.size())};
 }
 
 bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }
@@ -218,7 +226,7 @@ int unzip_centred(ot_tree* tree, int nvar, const double* zipped_dev, double* pad
     if (!tree || nvar <= 0 || nvar > 65535 || !zipped_dev || !padded_dev) return OT_E_BADARG;
     if (tree->host.leaves.size() * static_cast<size_t>(nvar) > 0x7fffffffu) return OT_E_UNSUPPORTED;   // one workgroup each
     if (int rc = ensure_device(tree)) return rc;
-    hipError_t e = launch_unzip_centred(dev_view(tree), tree->host.level_start, nvar, zipped_dev, padded_dev,
+    hipError_t e = launch_unzip_centred(dev_view(tree), tree->host.level_start, false, nvar, zipped_dev, padded_dev,
                                         static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
@@ -236,8 +244,8 @@ int rhs_eval(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, const
 {
     if (!tree || !kind_ok(kind) || !params || !padded_dev || !rhs_padded_dev) return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
-    RhsArgs a{padded_dev, rhs_padded_dev, nullptr, nullptr, rhs_padded_dev, 0.0, params->ko_sigma};
-    hipError_t e = launch_rhs(dev_view(tree), kind, false, kOutPadded, a, static_cast<hipStream_t>(hip_stream));
+    RhsArgs a{padded_dev, rhs_padded_dev, nullptr, nullptr, nullptr, rhs_padded_dev, 0.0, params->ko_sigma};
+    hipError_t e = launch_rhs(dev_view(tree), kind, false, false, kOutPadded, a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
@@ -246,8 +254,8 @@ int rhs_eval_zipped(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params
 {
     if (!tree || !kind_ok(kind) || !params || !zipped_dev || !rhs_zipped_dev) return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
-    RhsArgs a{zipped_dev, rhs_zipped_dev, nullptr, nullptr, rhs_zipped_dev, 0.0, params->ko_sigma};
-    hipError_t e = launch_rhs(dev_view(tree), kind, true, kOutZipped, a, static_cast<hipStream_t>(hip_stream));
+    RhsArgs a{zipped_dev, rhs_zipped_dev, nullptr, nullptr, nullptr, rhs_zipped_dev, 0.0, params->ko_sigma};
+    hipError_t e = launch_rhs(dev_view(tree), kind, true, false, kOutZipped, a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
@@ -279,13 +287,13 @@ int rk_step(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double
     // stage vectors ping-pong between sa and sb: a stage reads ghosts of the vector it was given
     // while writing the next one, so the two must be different arrays
     const RhsArgs st[4] = {
-        {u, sa, acc, u, sa, 0.5 * dt, sg},    // k1 = F(u):   acc = k1,        sa = u + dt/2 k1
-        {sa, sb, acc, u, sb, 0.5 * dt, sg},   // k2 = F(sa):  acc += 2 k2,     sb = u + dt/2 k2
-        {sb, sa, acc, u, sa, dt, sg},         // k3 = F(sb):  acc += 2 k3,     sa = u + dt k3
-        {sa, nullptr, acc, u, sb, dt / 6.0, sg}};   // k4 = F(sa):  u += dt/6 (acc + k4); sb is free scratch
+        {u, sa, acc, u, nullptr, sa, 0.5 * dt, sg},    // k1 = F(u):   acc = k1,        sa = u + dt/2 k1
+        {sa, sb, acc, u, nullptr, sb, 0.5 * dt, sg},   // k2 = F(sa):  acc += 2 k2,     sb = u + dt/2 k2
+        {sb, sa, acc, u, nullptr, sa, dt, sg},         // k3 = F(sb):  acc += 2 k3,     sa = u + dt k3
+        {sa, nullptr, acc, u, nullptr, sb, dt / 6.0, sg}};   // k4 = F(sa):  u += dt/6 (acc + k4); sb is free scratch
     const Epilogue ep[4] = {kRkFirst, kRkMiddle, kRkMiddle, kRkLast};
     for (int i = 0; i < 4; ++i) {
-        hipError_t e = launch_rhs(dv, kind, true, ep[i], st[i], s);
+        hipError_t e = launch_rhs(dv, kind, true, false, ep[i], st[i], s);
         if (e != hipSuccess) return hip_fail(e);
     }
     return OT_OK;
@@ -295,7 +303,8 @@ int rk_centred_workspace_bytes(const ot_tree* tree, ot_rhs_kind kind, size_t* by
 {
     size_t zipped3 = 0;
     if (int rc = rk_workspace_bytes(tree, kind, &zipped3)) return rc;
-    *bytes = zipped3 + static_cast<size_t>(ot_rhs_nvar_in(kind)) * tree->host.leaves.size() * 2744 * sizeof(double);
+    // three zipped vectors, then the padded blocks of the source leaves of the current stage vector
+    *bytes = zipped3 + static_cast<size_t>(ot_rhs_nvar_in(kind)) * tree->host.src_by_level.size() * 2744 * sizeof(double);
     return OT_OK;
 }
 
@@ -314,22 +323,21 @@ int rk_step_centred(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params
     double* acc = static_cast<double*>(workspace_dev);
     double* sa = acc + len;
     double* sb = sa + len;
-    double* pad = sb + len;                     // ghost-padded copy of the current stage vector
+    double* pad = sb + len;                     // padded source leaves of the current stage vector
     double* u = u_zipped_dev;
     const DeviceTree dv = dev_view(tree);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const double sg = params->ko_sigma;
-    // the padded copy decouples a stage's input from its output, so one stage vector would do; the
-    // two are kept so that the SYN24 scratch of the last stage (sb) never aliases its input
-    const double* stage_in[4] = {u, sa, sb, sa};
-    const RhsArgs st[4] = {{pad, sa, acc, u, sa, 0.5 * dt, sg},
-                           {pad, sb, acc, u, sb, 0.5 * dt, sg},
-                           {pad, sa, acc, u, sa, dt, sg},
-                           {pad, nullptr, acc, u, sb, dt / 6.0, sg}};
+    // per stage: the few leaves that serve as coarser sources are ghost-filled level by level into
+    // `pad`; the fused stage kernel then reads everything else straight from the zipped vector
+    const RhsArgs st[4] = {{u, sa, acc, u, pad, sa, 0.5 * dt, sg},
+                           {sa, sb, acc, u, pad, sb, 0.5 * dt, sg},
+                           {sb, sa, acc, u, pad, sa, dt, sg},
+                           {sa, nullptr, acc, u, pad, sb, dt / 6.0, sg}};
     const Epilogue ep[4] = {kRkFirst, kRkMiddle, kRkMiddle, kRkLast};
     for (int i = 0; i < 4; ++i) {
-        hipError_t e = launch_unzip_centred(dv, tree->host.level_start, nvar, stage_in[i], pad, s);
-        if (e == hipSuccess) e = launch_rhs(dv, kind, false, ep[i], st[i], s);
+        hipError_t e = launch_unzip_centred(dv, tree->host.src_level_start, true, nvar, st[i].in, pad, s);
+        if (e == hipSuccess) e = launch_rhs(dv, kind, true, true, ep[i], st[i], s);
         if (e != hipSuccess) return hip_fail(e);
     }
     return OT_OK;

@@ -49,12 +49,14 @@ struct BoxPlan {
     int32_t o1[8], o2[8], o3[8];             // per source: offset of its items inside its round's pass
     uint32_t mx[8], mpl[8];                  // per source: magic numbers for dividing by nx and by nx*ny
     int16_t sx[8], nx[8], sy[8], ny[8], sz[8], nz[8], fx0[8], fy0[8], fz0[8];
+    int16_t face_src[6];                     // for the q-th coarser face: which source (index into the list) it is
 };
 
 struct BlockInfo {       // per-workgroup copy of the block's table rows
     int32_t gt[27 * 5];
     int32_t cs[32];      // [0..15] coarse sources: {leaf id, packed region range} x 8, id < 0 ends the
                          // list; [16] number of coarser faces, [17..28] {face, leaf id} pairs
+    int32_t slot[8];     // centred ghost rule: where the padded block of coarse source s sits (src_slot of its id)
     uint32_t level, ax, ay, az;
     double lag[36];
     BoxPlan box;         // filled by make_box_plan()
@@ -110,6 +112,10 @@ __device__ __forceinline__ void load_block_info(BlockInfo& bi, const DeviceTree&
     if (tid < 27 * 5) bi.gt[tid] = tr.ghost[b * (27 * 5) + tid];
     if (tid >= 192 && tid < 192 + 36) bi.lag[tid - 192] = c_lag[tid - 192];
     if (tid >= 256 && tid < 256 + 32) bi.cs[tid - 256] = tr.coarse[b * 32 + (tid - 256)];
+    if (tid >= 384 && tid < 384 + 8) {
+        const int32_t id = tr.coarse[b * 32 + 2 * (tid - 384)];
+        bi.slot[tid - 384] = id >= 0 ? tr.src_slot[id] : -1;
+    }
     if (tid == 320) {
         const ot_leaf lf = tr.leaves[b];
         bi.level = lf.level; bi.ax = lf.ix; bi.ay = lf.iy; bi.az = lf.iz;
@@ -287,6 +293,11 @@ __device__ void make_box_plan(BlockInfo& bi)
         bp.rbeg[nr] = ns;
     }
     bp.nround = nr;
+    for (int q = 0; q < bi.cs[16]; ++q) {
+        int s = 0;
+        while (s < ns - 1 && bi.cs[2 * s] != bi.cs[18 + 2 * q]) ++s;
+        bp.face_src[q] = s;
+    }
 }
 // the largest single box (11 x 11 x 3 or 3) must fit: 968 + 704
 static_assert(NPT * 121 + 64 * 11 <= SCRATCH && BLK + 64 * 11 <= SCRATCH, "interpolation staging");
@@ -340,9 +351,11 @@ __device__ __forceinline__ void interp_boxes(double* tile, double* scratch, cons
 // The same for the centred variant of the ghost rule: the source is the coarser leaf's PADDED block
 // (cpad, 14^3, filled by an earlier launch), every odd fine coordinate f takes the centred stencil
 // on coarse nodes c0-2 .. c0+3, c0 = f >> 1, which may reach into that leaf's ghost layers.
-// The box needs coarse nodes clo .. chi per axis, at most 13 of them.
-constexpr int CBOX = 13;
-constexpr int CT1 = CBOX * CBOX * NP, CT2 = CBOX * NP * NP;      // staging after the x pass / the y pass
+// A box is 3 or 11 fine points wide per axis and needs 7 or 11 coarse nodes there (clo .. chi), and
+// at least one axis is 3 wide: the coarse sub-box and the x- and y-pass results take at most 847
+// doubles each, and two of the three are alive at a time.
+constexpr int CENTRED_STAGING = 2 * 847;
+static_assert(CENTRED_STAGING <= SCRATCH, "centred interpolation staging");
 __device__ __forceinline__ double centred_line(const double* v, int st, int f, int clo, const double* lag)
 {
     const int c0 = f >> 1;
@@ -360,15 +373,15 @@ __device__ __forceinline__ double centred_line(const double* v, int st, int f, i
 __device__ __forceinline__ void interp_box_centred(double* tile, double* scratch, const BlockInfo& bi, const double* cpad,
                                                    int sx, int nx, int sy, int ny, int sz, int nz, int tid)
 {
-    double* T1 = scratch;            // after the x pass  [cz][cy][tx]
-    double* T2 = T1 + CT1;           // after the y pass  [cz][ty][tx]
-    double* C = T2;                  // the coarse sub-box [cz][cy][cx]: dead once the x pass is done
     const int fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
     const int fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
     const int fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
     const int clx = (fx0 >> 1) - 2, ncx = ((fx0 + nx - 1) >> 1) + 3 - clx + 1;
     const int cly = (fy0 >> 1) - 2, ncy = ((fy0 + ny - 1) >> 1) + 3 - cly + 1;
     const int clz = (fz0 >> 1) - 2, ncz = ((fz0 + nz - 1) >> 1) + 3 - clz + 1;
+    double* T1 = scratch;                    // after the x pass  [cz][cy][tx]
+    double* T2 = T1 + ncz * ncy * nx;        // after the y pass  [cz][ty][tx]
+    double* C = T2;                          // the coarse sub-box [cz][cy][cx]: dead once the x pass is done
     const uint32_t mcx = div_magic(ncx), mcxy = div_magic(ncx * ncy), mx = div_magic(nx), mxy = div_magic(nx * ny);
     __syncthreads();                 // everybody is done with the staging arrays
     for (int q = tid; q < ncz * ncy * ncx; q += NTHREADS) {
@@ -389,6 +402,32 @@ __device__ __forceinline__ void interp_box_centred(double* tile, double* scratch
     for (int q = tid; q < nz * ny * nx; q += NTHREADS) {         // z pass, into the tile
         const int tz = div_by(q, mxy), r = q - tz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
         tile[tidx(sz + tz, sy + ty, sx + tx)] = centred_line(&T2[r], nx * ny, fz0 + tz, clz, bi.lag);
+    }
+}
+
+// every coarser source leaf of the block, one after the other; pbase = one variable's compact array of
+// padded source leaves
+__device__ __forceinline__ void interp_boxes_centred(double* tile, double* scratch, const BlockInfo& bi,
+                                                     const double* __restrict__ pbase, int tid)
+{
+    const BoxPlan& bp = bi.box;
+    const int ns = bp.rbeg[bp.nround];
+#pragma unroll 1
+    for (int s = 0; s < ns; ++s)
+        interp_box_centred(tile, scratch, bi, pbase + (int64_t)bi.slot[s] * PBLK, bp.sx[s], bp.nx[s], bp.sy[s], bp.ny[s],
+                           bp.sz[s], bp.nz[s], tid);
+}
+// the same where only the face slabs of the tile are read: one 3 x 8 x 8 box per coarser face
+__device__ __forceinline__ void interp_faces_centred(double* tile, double* scratch, const BlockInfo& bi,
+                                                     const double* __restrict__ pbase, int tid)
+{
+    const int n = bi.cs[16];
+#pragma unroll 1
+    for (int q = 0; q < n; ++q) {
+        const int face = bi.cs[17 + 2 * q], ax = face >> 1, s0 = (face & 1) ? PAD + NPT : 0;
+        const int sx = ax == 0 ? s0 : PAD, sy = ax == 1 ? s0 : PAD, sz = ax == 2 ? s0 : PAD;
+        const int nx = ax == 0 ? PAD : NPT, ny = ax == 1 ? PAD : NPT, nz = ax == 2 ? PAD : NPT;
+        interp_box_centred(tile, scratch, bi, pbase + (int64_t)bi.slot[bi.box.face_src[q]] * PBLK, sx, nx, sy, ny, sz, nz, tid);
     }
 }
 
@@ -423,10 +462,12 @@ __device__ __forceinline__ void coarse_prefetch(double (&cv)[CPRE], const BlockI
         if (q < n) cv[q] = ldg(base, ((uint32_t)bi.cs[18 + 2 * q] * BLK + tid) * 8u);
 }
 
-template <bool ZIN, int NPLAN, int USE>
+// CENTRED: ghost values from coarser leaves follow the centred rule and come from pbase (that
+// variable's padded source leaves).
+template <bool ZIN, int NPLAN, int USE, bool CENTRED = false>
 __device__ __forceinline__ void commit(double* tile, double* scratch, const BlockInfo& bi, const FillPlan<NPLAN>& fp,
                                        const double (&v)[NPLAN], const double (&cv)[CPRE], bool have_cv,
-                                       const double* __restrict__ base, int tid)
+                                       const double* __restrict__ base, int tid, const double* __restrict__ pbase = nullptr)
 {
 #pragma unroll
     for (int m = 0; m < USE; ++m) {
@@ -436,7 +477,10 @@ __device__ __forceinline__ void commit(double* tile, double* scratch, const Bloc
     }
     if (!ZIN || bi.cs[0] < 0) return;
     // Control flow below is uniform over the workgroup.
-    if (USE == PLAN_FACE) {
+    if (CENTRED) {
+        if (USE == PLAN_FACE) interp_faces_centred(tile, scratch, bi, pbase, tid);
+        else interp_boxes_centred(tile, scratch, bi, pbase, tid);
+    } else if (USE == PLAN_FACE) {
         // Faces only: each face neighbour that is coarser supplies a 3 x 8 x 8 slab.  Wavefront w
         // owns the coarse plane cz = w: it interpolates that plane in x and then in y out of its
         // own staging area with no workgroup barrier; only the z pass, which combines the planes,
@@ -683,9 +727,10 @@ __device__ __forceinline__ double syn24_combine(const Syn24Part& p, int f, doubl
 constexpr int NSTREAM = 25;
 __device__ __forceinline__ int syn24_stream(int t) { return t == 0 ? 10 : (t <= 10 ? 10 - t : 34 - t); }
 
-template <int KIND, bool ZIN, int EPI>
+template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
 __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr, RhsArgs a)
 {
+    static_assert(ZIN || !CENTRED, "the centred ghost rule applies to zipped input");
     constexpr int NBUF = KIND == OT_RHS_SYN24 ? 2 : 1;
     __shared__ double tiles[NBUF * TILE];
     __shared__ double scratch[(ZIN || KIND == OT_RHS_SYN24) ? SCRATCH : 1];
@@ -722,10 +767,13 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
     auto var_base = [&](int v) -> const double* {
         return ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK;
     };
+    auto pad_base = [&](int v) -> const double* {   // centred rule: variable v's padded source leaves
+        return CENTRED ? a.pad_src + (int64_t)v * tr.n_src * PBLK : nullptr;
+    };
     auto stage = [&](int v) {   // bring variable v into tile buffer 0 (barrier before and after)
         __syncthreads();
         prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(v), tid);
-        commit<ZIN, NPLAN, PLAN_FACE>(tiles, scratch, bi, fp, pv, cv, false, var_base(v), tid);
+        commit<ZIN, NPLAN, PLAN_FACE, CENTRED>(tiles, scratch, bi, fp, pv, cv, false, var_base(v), tid, pad_base(v));
         __syncthreads();
     };
     auto centre = [&](int v) -> double {   // this thread's own value of variable v
@@ -787,7 +835,7 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
             if (t + 1 < NSTREAM) {
                 f1 = syn24_stream(t + 1);
                 prefetch<NPLAN, NEXT_USE>(pv, fp, var_base(f1), tid);
-                if (ZIN && NEXT_USE == PLAN_FACE) coarse_prefetch(cv, bi, var_base(f1), tid);
+                if (ZIN && !CENTRED && NEXT_USE == PLAN_FACE) coarse_prefetch(cv, bi, var_base(f1), tid);
             }
             l.unext = centre((f + 11) % 24);
             l.eo = epi_prefetch<EPI>(a, nb, f, o8);
@@ -811,7 +859,7 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
             const double lap = fma(2.0, off, p.diag);
             stg(stash_base(10 + f), s8, lap);
             emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l.unext), l.eo);
-            commit<ZIN, NPLAN, NEXT_USE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, NEXT_USE == PLAN_FACE, var_base(f1), tid);
+            commit<ZIN, NPLAN, NEXT_USE, CENTRED>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, NEXT_USE == PLAN_FACE, var_base(f1), tid, pad_base(f1));
             __syncthreads();
         };
         // pass over a variable without second derivatives (23..10)
@@ -824,7 +872,7 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
             const Syn24Part p = syn24_axes<false>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
             emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, l.lap, halpha, l.unext), l.eo);
             if (t + 1 < NSTREAM) {
-                commit<ZIN, NPLAN, PLAN_FACE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, true, var_base(f1), tid);
+                commit<ZIN, NPLAN, PLAN_FACE, CENTRED>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, true, var_base(f1), tid, pad_base(f1));
                 __syncthreads();
             }
         };
@@ -832,11 +880,12 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
         {   // pass 0: gradient of variable 10 only
             const int f = syn24_stream(0), f1 = syn24_stream(1);
             prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(f), tid);
-            commit<ZIN, NPLAN, PLAN_FACE>(tiles, scratch, bi, fp, pv, cv, false, var_base(f), tid);
+            if (CENTRED) __syncthreads();            // the box plan, made by one thread, is read in this commit already
+            commit<ZIN, NPLAN, PLAN_FACE, CENTRED>(tiles, scratch, bi, fp, pv, cv, false, var_base(f), tid, pad_base(f));
             __syncthreads();
             prefetch<NPLAN, PLAN_EDGE>(pv, fp, var_base(f1), tid);
             nx = d1_at(tiles, c, 1, ih); ny = d1_at(tiles, c, RS, ih); nz = d1_at(tiles, c, PS, ih);
-            commit<ZIN, NPLAN, PLAN_EDGE>(tiles + TILE, scratch, bi, fp, pv, cv, false, var_base(f1), tid);
+            commit<ZIN, NPLAN, PLAN_EDGE, CENTRED>(tiles + TILE, scratch, bi, fp, pv, cv, false, var_base(f1), tid, pad_base(f1));
             __syncthreads();
         }
 #pragma unroll 1
@@ -887,18 +936,22 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, con
 // Level-ordered ghost fill, centred variant: launched once per level, coarsest first; `blocks` lists
 // the blocks of that level.  Copies and injections as in k_unzip; boxes that come from a coarser
 // leaf are interpolated from that leaf's padded block, which an earlier launch has written.
+// SOURCES: only the source leaves are filled, into a compact array indexed by src_slot.
+template <bool SOURCES>
 __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const int32_t* __restrict__ blocks, int nvar,
                                                             const double* __restrict__ zipped, double* padded)
 {
     __shared__ double tile[TILE];
-    __shared__ double scratch[CT1 + CT2];
+    __shared__ double scratch[CENTRED_STAGING];
     __shared__ BlockInfo bi;
     __shared__ uint32_t plan_src[PLAN_FULL * NTHREADS];
     const int tid = threadIdx.x;
     // variable fastest in the launch order, as in k_unzip
     const int64_t q = blockIdx.x / nvar, v = blockIdx.x - q * nvar, b = blocks[q], nb = tr.nb;
+    const int64_t nout = SOURCES ? tr.n_src : nb;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
+    if (tid == 0) make_box_plan(bi);
     FillPlan<PLAN_FULL> fp;
     fp.src = plan_src;
     make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);
@@ -906,19 +959,16 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const
     prefetch<PLAN_FULL, PLAN_FULL>(pv, fp, zipped + v * nb * BLK, tid);
     double cv[CPRE];
     commit<false, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, zipped, tid);   // stores only
+    __syncthreads();                                 // the box plan is complete
+    const int ns = bi.box.rbeg[bi.box.nround];
 #pragma unroll 1
-    for (int sidx = 0; sidx < 8; ++sidx) {
-        const int32_t id = bi.cs[2 * sidx];
-        if (id < 0) break;
-        const int pk = bi.cs[2 * sidx + 1];
-        const int rxl = pk & 3, rxh = (pk >> 2) & 3, ryl = (pk >> 4) & 3, ryh = (pk >> 6) & 3, rzl = (pk >> 8) & 3, rzh = (pk >> 10) & 3;
-        const int sx = rxl == 0 ? 0 : (rxl == 1 ? PAD : PAD + NPT), ex = rxh == 0 ? PAD : (rxh == 1 ? PAD + NPT : NP);
-        const int sy = ryl == 0 ? 0 : (ryl == 1 ? PAD : PAD + NPT), ey = ryh == 0 ? PAD : (ryh == 1 ? PAD + NPT : NP);
-        const int sz = rzl == 0 ? 0 : (rzl == 1 ? PAD : PAD + NPT), ez = rzh == 0 ? PAD : (rzh == 1 ? PAD + NPT : NP);
-        interp_box_centred(tile, scratch, bi, padded + (v * nb + id) * PBLK, sx, ex - sx, sy, ey - sy, sz, ez - sz, tid);
+    for (int s = 0; s < ns; ++s) {
+        const int64_t src = SOURCES ? bi.slot[s] : bi.cs[2 * s];
+        interp_box_centred(tile, scratch, bi, padded + (v * nout + src) * PBLK, bi.box.sx[s], bi.box.nx[s], bi.box.sy[s],
+                           bi.box.ny[s], bi.box.sz[s], bi.box.nz[s], tid);
     }
     __syncthreads();
-    double* out = padded + (v * nb + b) * PBLK;
+    double* out = padded + (v * nout + (SOURCES ? (int64_t)tr.src_slot[b] : b)) * PBLK;
 #pragma unroll
     for (int m = 0; m < PLAN_FULL; ++m) {
         const int p = tid + m * NTHREADS;
@@ -936,16 +986,26 @@ __global__ __launch_bounds__(NTHREADS) void k_zip(int64_t nblocks, const double*
     zipped[q * BLK + tid] = padded[q * PBLK + ((k + PAD) * NP + (j + PAD)) * NP + (i + PAD)];
 }
 
-template <int KIND, bool ZIN, int EPI>
+template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
 hipError_t launch_one(const DeviceTree& t, const RhsArgs& a, hipStream_t s)
 {
-    hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
+    hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, CENTRED>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
     return hipGetLastError();
 }
 
 template <int KIND>
-hipError_t launch_kind(const DeviceTree& t, bool zin, Epilogue ep, const RhsArgs& a, hipStream_t s)
+hipError_t launch_kind(const DeviceTree& t, bool zin, bool centred, Epilogue ep, const RhsArgs& a, hipStream_t s)
 {
+    if (centred) {
+        if (!zin || !a.pad_src) return hipErrorInvalidValue;
+        switch (ep) {
+        case kOutZipped: return launch_one<KIND, true, kOutZipped, true>(t, a, s);
+        case kRkFirst: return launch_one<KIND, true, kRkFirst, true>(t, a, s);
+        case kRkMiddle: return launch_one<KIND, true, kRkMiddle, true>(t, a, s);
+        case kRkLast: return launch_one<KIND, true, kRkLast, true>(t, a, s);
+        default: return hipErrorInvalidValue;
+        }
+    }
     if (!zin) {
         switch (ep) {
         case kOutPadded: return launch_one<KIND, false, kOutPadded>(t, a, s);
@@ -974,15 +1034,19 @@ hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, dou
     return hipGetLastError();
 }
 
-hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, int nvar, const double* zipped,
-                                double* padded, hipStream_t s)
+hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, bool sources_only, int nvar,
+                                const double* zipped, double* padded, hipStream_t s)
 {
     if (t.nb <= 0 || nvar <= 0) return hipSuccess;
     for (int l = 0; l < 20; ++l) {                   // coarsest level first; the stream orders the launches
         const int64_t n = level_start[l + 1] - level_start[l];
         if (n <= 0) continue;
-        hipLaunchKernelGGL(k_unzip_centred, dim3((unsigned)(n * nvar)), dim3(NTHREADS), 0, s, t,
-                           t.by_level + level_start[l], nvar, zipped, padded);
+        if (sources_only)
+            hipLaunchKernelGGL(k_unzip_centred<true>, dim3((unsigned)(n * nvar)), dim3(NTHREADS), 0, s, t,
+                               t.src_by_level + level_start[l], nvar, zipped, padded);
+        else
+            hipLaunchKernelGGL(k_unzip_centred<false>, dim3((unsigned)(n * nvar)), dim3(NTHREADS), 0, s, t,
+                               t.by_level + level_start[l], nvar, zipped, padded);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -997,14 +1061,15 @@ hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, doubl
     return hipGetLastError();
 }
 
-hipError_t launch_rhs(const DeviceTree& t, ot_rhs_kind kind, bool in_zipped, Epilogue ep, const RhsArgs& args, hipStream_t s)
+hipError_t launch_rhs(const DeviceTree& t, ot_rhs_kind kind, bool in_zipped, bool centred, Epilogue ep, const RhsArgs& args,
+                      hipStream_t s)
 {
     if (t.nb <= 0) return hipSuccess;
     switch (kind) {
-    case OT_RHS_DERIVS: return launch_kind<OT_RHS_DERIVS>(t, in_zipped, ep, args, s);
-    case OT_RHS_WAVE: return launch_kind<OT_RHS_WAVE>(t, in_zipped, ep, args, s);
-    case OT_RHS_BURGERS: return launch_kind<OT_RHS_BURGERS>(t, in_zipped, ep, args, s);
-    case OT_RHS_SYN24: return launch_kind<OT_RHS_SYN24>(t, in_zipped, ep, args, s);
+    case OT_RHS_DERIVS: return launch_kind<OT_RHS_DERIVS>(t, in_zipped, centred, ep, args, s);
+    case OT_RHS_WAVE: return launch_kind<OT_RHS_WAVE>(t, in_zipped, centred, ep, args, s);
+    case OT_RHS_BURGERS: return launch_kind<OT_RHS_BURGERS>(t, in_zipped, centred, ep, args, s);
+    case OT_RHS_SYN24: return launch_kind<OT_RHS_SYN24>(t, in_zipped, centred, ep, args, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -14,6 +14,10 @@ struct DeviceTree {
     const int32_t* coarse;   // [nb][32] coarser sources with their boxes, and coarser faces (see HostTree)
     const int32_t* by_level; // [nb] block ids sorted by level
     int64_t nb;
+    // centred ghost rule: the leaves that are a coarser source of some block ("source leaves")
+    const int32_t* src_slot;     // [nb] position of a source leaf in a compact padded array, -1 for the others
+    const int32_t* src_by_level; // [n_src] ids of the source leaves sorted by level
+    int64_t n_src;
 };
 
 // how the right-hand side leaves the kernel
@@ -30,6 +34,7 @@ struct RhsArgs {
     double* out;        // kOutPadded / kOutZipped: result; kRkFirst / kRkMiddle: next stage vector
     double* acc;        // Runge-Kutta accumulator (zipped)
     double* u;          // state at the start of the step (zipped); written by kRkLast
+    const double* pad_src;   // centred ghost rule only: padded blocks of the source leaves of `in`, [V][n_src][2744]
     double* stash;      // SYN24 only: array shaped like `out` whose variables 10..19 may be used as
                         // scratch until their final values are written (may be `out` itself)
     double c;           // dt/2, dt or dt/6
@@ -37,12 +42,15 @@ struct RhsArgs {
 };
 
 hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, double* padded, hipStream_t s);
-// level-ordered ghost fill with centred coarse-lattice stencils; level_start[21] as in HostTree
-hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, int nvar, const double* zipped,
-                                double* padded, hipStream_t s);
+// level-ordered ghost fill with centred coarse-lattice stencils; level_start[21] as in HostTree.
+// sources_only = false: every block, padded [nvar][nb][2744];  true: only the source leaves (level_start
+// then refers to src_by_level), padded [nvar][n_src][2744] indexed by src_slot
+hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, bool sources_only, int nvar,
+                                const double* zipped, double* padded, hipStream_t s);
 hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, double* zipped, hipStream_t s);
-// in_zipped = false: args.in is padded; true: args.in is zipped
-hipError_t launch_rhs(const DeviceTree& t, ot_rhs_kind kind, bool in_zipped, Epilogue ep, const RhsArgs& args,
-                      hipStream_t s);
+// in_zipped = false: args.in is padded; true: args.in is zipped.  centred (zipped input only): ghost
+// values from coarser leaves follow the centred rule and are read from args.pad_src
+hipError_t launch_rhs(const DeviceTree& t, ot_rhs_kind kind, bool in_zipped, bool centred, Epilogue ep,
+                      const RhsArgs& args, hipStream_t s);
 
 }  // namespace octfd

@@ -217,6 +217,27 @@ void make_level_lists(HostTree& t)
     for (int l = 0; l <= 20; ++l) t.level_start[l] = count[l];
     t.by_level.assign(nb, 0);
     for (size_t b = 0; b < nb; ++b) t.by_level[count[t.leaves[b].level]++] = static_cast<int32_t>(b);
+
+    // the source leaves, found through the coarse-source lists of all blocks
+    t.src_slot.assign(nb, -1);
+    for (size_t b = 0; b < nb; ++b)
+        for (int s = 0; s < 8; ++s) {
+            const int32_t id = t.coarse[b * kCoarseRow + 2 * s];
+            if (id < 0) break;
+            t.src_slot[id] = 0;
+        }
+    int32_t n_src = 0;
+    int64_t scount[21] = {};
+    for (size_t b = 0; b < nb; ++b)
+        if (t.src_slot[b] == 0) {
+            t.src_slot[b] = n_src++;
+            ++scount[t.leaves[b].level + 1];
+        }
+    for (int l = 1; l <= 20; ++l) scount[l] += scount[l - 1];
+    for (int l = 0; l <= 20; ++l) t.src_level_start[l] = scount[l];
+    t.src_by_level.assign(n_src, 0);
+    for (size_t b = 0; b < nb; ++b)
+        if (t.src_slot[b] >= 0) t.src_by_level[scount[t.leaves[b].level]++] = static_cast<int32_t>(b);
 }
 
 int build_tree(const ot_build_params& p, HostTree& out)

@@ -28,6 +28,11 @@ struct HostTree {
     // by_level[level_start[l] .. level_start[l+1]).  Used by the level-ordered ghost fill.
     std::vector<int32_t> by_level;
     int64_t level_start[21] = {};
+    // "Source leaves": the leaves that some block takes ghost values from by coarse-to-fine
+    // interpolation.  src_slot[b] numbers them (Morton order), -1 for all other leaves;
+    // src_by_level / src_level_start list them by level like by_level / level_start.
+    std::vector<int32_t> src_slot, src_by_level;
+    int64_t src_level_start[21] = {};
 };
 
 // Each returns an OT_* status.

@@ -119,3 +119,17 @@ def test_two_ghost_rules_on_a_plane_wave_over_many_steps(dev):
           % (err["clamped", 64], err["centred", 64], err["centred", 1024]), flush=True)
     assert err["centred", 64] < err["clamped", 64] / 10.0
     assert err["centred", 1024] < 1e-4
+
+
+def test_centred_step_on_a_uniform_tree_equals_the_clamped_step(dev):
+    # no leaf is a coarser source: the compact padded array is empty and both rules do the same arithmetic
+    t = octfd.Tree.build(3, 3, np.zeros((1, 3), np.uint32), np.zeros(0, np.uint32))
+    assert t.rk_centred_workspace_bytes(1) == t.rk_workspace_bytes(1)
+    u = torch.from_numpy(np.random.default_rng(4).standard_normal((2, t.n, 8, 8, 8))).to(dev)
+    a, b = u.clone(), u.clone()
+    ws = torch.empty(t.rk_workspace_bytes(1) // 8, dtype=torch.float64, device=dev)
+    dt = sd.time_step(3)
+    t.rk_step(1, a, dt, ws, sigma=0.4)
+    t.rk_step_centred(1, b, dt, ws, sigma=0.4)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.isfinite(a).all()

@@ -308,20 +308,25 @@ __device__ __forceinline__ void interp_boxes(double* tile, double* scratch, cons
                                              const double* __restrict__ base, int tid)
 {
     const BoxPlan& bp = bi.box;
+    double cv[ROUND_SRC];
+    auto request = [&](int r) {                  // the source leaves of round r, one element per thread and leaf
+        const int s0 = bp.rbeg[r], s1 = bp.rbeg[r + 1];
+#pragma unroll
+        for (int q = 0; q < ROUND_SRC; ++q)
+            if (s0 + q < s1) cv[q] = ldg(base, ((uint32_t)bi.cs[2 * (s0 + q)] * BLK + tid) * 8u);
+    };
+    if (bp.nround > 0) request(0);
 #pragma unroll 1
     for (int r = 0; r < bp.nround; ++r) {
         const int s0 = bp.rbeg[r], s1 = bp.rbeg[r + 1];
         double* A = scratch;
         double* B = scratch + bp.bstart[r];
-        double cv[ROUND_SRC];
-#pragma unroll
-        for (int q = 0; q < ROUND_SRC; ++q)
-            if (s0 + q < s1) cv[q] = ldg(base, ((uint32_t)bi.cs[2 * (s0 + q)] * BLK + tid) * 8u);
         __syncthreads();                         // everybody is done with the staging area
 #pragma unroll
         for (int q = 0; q < ROUND_SRC; ++q)
             if (s0 + q < s1) A[q * BLK + tid] = cv[q];
         __syncthreads();
+        if (r + 1 < bp.nround) request(r + 1);   // in flight during the three sweeps of this round
         for (int q = tid; q < bp.n1[r]; q += NTHREADS) {             // x pass, item (source, row = cz*8 + cy, tx)
             int s = s0;
             while (s + 1 < s1 && q >= bp.o1[s + 1]) ++s;

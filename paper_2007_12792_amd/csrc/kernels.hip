@@ -738,7 +738,11 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
     static_assert(ZIN || !CENTRED, "the centred ghost rule applies to zipped input");
     constexpr int NBUF = KIND == OT_RHS_SYN24 ? 2 : 1;
     __shared__ double tiles[NBUF * TILE];
-    __shared__ double scratch[(ZIN || KIND == OT_RHS_SYN24) ? SCRATCH : 1];
+    // SYN24 keeps wy / wz here and stages whole boxes of coarser leaves; the other kinds read face slabs
+    // only, whose interpolation needs 2,048 doubles (and lets three workgroups share a compute unit)
+    constexpr int FACE_STAGING = 1024 + 2 * 512;
+    static_assert(FACE_STAGING >= 810, "centred interpolation of one 3 x 8 x 8 face slab");
+    __shared__ double scratch[KIND == OT_RHS_SYN24 ? SCRATCH : (ZIN ? FACE_STAGING : 1)];
     __shared__ BlockInfo bi;
     // second derivatives (SYN24 only) read the edge slabs of the tile too
     constexpr int NPLAN = KIND == OT_RHS_SYN24 ? PLAN_EDGE : PLAN_FACE;
@@ -751,7 +755,7 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
     if (b >= nb) return;                             // uniform over the workgroup
     load_block_info(bi, tr, b, tid);
     __syncthreads();
-    if (tid == 0) make_box_plan(bi);                 // read only after the next barrier
+    if (tid == 0 && (KIND == OT_RHS_SYN24 || CENTRED)) make_box_plan(bi);   // read only after the next barrier
 
     int i, j, k;
     point_of(tid, i, j, k);

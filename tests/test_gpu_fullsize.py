@@ -52,3 +52,20 @@ def test_config5_rhs_sampled_and_rk_step(orc, dev):  # noqa: F811
     print("rk_step C5: worst |diff|/bound = %.3g" % float((err / bound).max()), flush=True)
     assert bool((err <= bound).all())
     assert float((got - ud).abs().max()) > 0
+
+
+def test_centred_step_of_the_wave_system_on_the_largest_tree(orc, dev):  # noqa: F811
+    """rk_step_centred on the 102,075-block tree (seven levels of source leaves), two fields so that the
+    oracle, which pads every block, fits in memory and finishes in seconds; every element is compared."""
+    p = sd.tree_params("C5")
+    to, tg = orc.Tree.build(**p), octfd.Tree.build(**p)
+    x, y, z = sd.node_coords(to.leaves)
+    u = torch.stack([torch.sin(2 * np.pi * (x + 2 * y)) + 0.1 * torch.cos(6 * np.pi * z), torch.cos(2 * np.pi * (y - z))]).contiguous()
+    dt = sd.time_step(9)
+    print("oracle step", flush=True)
+    want = to.rk4_step_centred(1, u.numpy(), dt, sd.KO_SIGMA)
+    ud = u.to(dev)
+    ws = torch.empty(tg.rk_centred_workspace_bytes(1) // 8, dtype=torch.float64, device=dev)
+    tg.rk_step_centred(1, ud, dt, ws, sigma=sd.KO_SIGMA)
+    torch.cuda.synchronize()
+    assert_close(ud.cpu().numpy(), want, "C5 tree, WAVE, rk_step_centred")

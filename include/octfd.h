@@ -19,6 +19,8 @@
  *   - device entry points only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
  *     default stream).  They do not synchronise and do not allocate, except that the first device
  *     call on a tree (or octree_upload) copies the index tables to the device, synchronously.
+ *     That device must be the current one in every later call on the tree (else OT_E_UNSUPPORTED).
+ *   - calls that use the same tree, plan or workspace must not overlap in time.
  *   - layouts (x fastest): zipped  [var][block][k][j][i]     8*8*8   doubles per block and variable
  *                          padded  [var][block][kk][jj][ii]  14*14*14, (ii,jj,kk) = (i,j,k)+3
  *     blocks are stored in Morton order of their anchors (x least significant bit).

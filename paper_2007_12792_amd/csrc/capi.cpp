@@ -42,9 +42,18 @@ int hip_fail(hipError_t e)
                                                                                                     : OT_E_HIP;
 }
 
+// the tables live on the device that was current at the first device call; later calls must run there
+int same_device(int device)
+{
+    int cur = -1;
+    const hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return hip_fail(e);
+    return cur == device ? OT_OK : OT_E_UNSUPPORTED;
+}
+
 int ensure_device(ot_tree* t)
 {
-    if (t->device >= 0) return OT_OK;
+    if (t->device >= 0) return same_device(t->device);
     int ndev = 0;
     hipError_t e = hipGetDeviceCount(&ndev);
     if (e != hipSuccess) return hip_fail(e);
@@ -63,7 +72,7 @@ int ensure_device(ot_tree* t)
     size_t off[7] = {0};
     for (int i = 0; i < 6; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
     char* base = nullptr;
-    if ((e = hipMalloc(reinterpret_cast<void**>(&base), off[6] + 256)) != hipSuccess) return hip_fail(e);
+    if ((e = hipMalloc(reinterpret_cast<void**>(&base), off[6])) != hipSuccess) return hip_fail(e);
     for (int i = 0; i < 6 && e == hipSuccess; ++i)
         if (bytes[i]) e = hipMemcpy(base + off[i], part[i], bytes[i], hipMemcpyHostToDevice);
     if (e != hipSuccess) {
@@ -82,7 +91,7 @@ int ensure_device(ot_tree* t)
 
 int ensure_device(ot_transfer* p)
 {
-    if (p->device >= 0) return OT_OK;
+    if (p->device >= 0) return same_device(p->device);
     int ndev = 0;
     hipError_t e = hipGetDeviceCount(&ndev);
     if (e != hipSuccess) return hip_fail(e);

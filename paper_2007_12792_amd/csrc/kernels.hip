@@ -243,6 +243,10 @@ __device__ __forceinline__ void make_plan_padded(FillPlan<NPLAN>& fp, int tid)
 }
 
 
+// q / d for the few divisors that occur here (3, 8, 11, 14 and their pairwise products), q < 65536
+__device__ __forceinline__ uint32_t div_magic(uint32_t d) { return 0xffffffffu / d + 1u; }
+__device__ __forceinline__ int div_by(int q, uint32_t magic) { return (int)__umulhi((uint32_t)q, magic); }
+
 // Interpolation of the boxes of the padded block that come from coarser leaves (every such leaf
 // covers one box; a coarser leaf spans 16 fine points per axis and never contains the block itself,
 // so a box is 3 or 11 points wide per axis and at least one axis is 3 wide).
@@ -251,9 +255,6 @@ __device__ __forceinline__ void make_plan_padded(FillPlan<NPLAN>& fp, int tid)
 // source, and all source leaves of a round are requested from memory together.
 // Staging per round: region A holds the coarse leaves (512 each) and, after the x pass, the y-pass
 // results; region B, behind it, holds the x-pass results.
-// q / d for the few divisors that occur here (3, 8, 11, 14 and their pairwise products), q < 65536
-__device__ __forceinline__ uint32_t div_magic(uint32_t d) { return 0xffffffffu / d + 1u; }
-__device__ __forceinline__ int div_by(int q, uint32_t magic) { return (int)__umulhi((uint32_t)q, magic); }
 // done by one thread per block, once: boxes from the packed region ranges, greedy rounds in list order
 __device__ void make_box_plan(BlockInfo& bi)
 {

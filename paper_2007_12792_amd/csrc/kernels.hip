@@ -376,64 +376,116 @@ __device__ __forceinline__ double centred_line(const double* v, int st, int f, i
     acc = fma(w[5], p[5 * st], acc);
     return acc;
 }
-__device__ __forceinline__ void interp_box_centred(double* tile, double* scratch, const BlockInfo& bi, const double* cpad,
-                                                   int sx, int nx, int sy, int ny, int sz, int nz, int tid)
-{
-    const int fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
-    const int fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
-    const int fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
-    const int clx = (fx0 >> 1) - 2, ncx = ((fx0 + nx - 1) >> 1) + 3 - clx + 1;
-    const int cly = (fy0 >> 1) - 2, ncy = ((fy0 + ny - 1) >> 1) + 3 - cly + 1;
-    const int clz = (fz0 >> 1) - 2, ncz = ((fz0 + nz - 1) >> 1) + 3 - clz + 1;
-    double* T1 = scratch;                    // after the x pass  [cz][cy][tx]
-    double* T2 = T1 + ncz * ncy * nx;        // after the y pass  [cz][ty][tx]
-    double* C = T2;                          // the coarse sub-box [cz][cy][cx]: dead once the x pass is done
-    const uint32_t mcx = div_magic(ncx), mcxy = div_magic(ncx * ncy), mx = div_magic(nx), mxy = div_magic(nx * ny);
-    __syncthreads();                 // everybody is done with the staging arrays
-    for (int q = tid; q < ncz * ncy * ncx; q += NTHREADS) {
-        const int cz = div_by(q, mcxy), r = q - cz * ncx * ncy, cy = div_by(r, mcx), cx = r - cy * ncx;
-        C[q] = cpad[((clz + cz + PAD) * NP + (cly + cy + PAD)) * NP + (clx + cx + PAD)];
+// One box and its coarse sub-box.  The interpolation is split in two so that the memory latency of
+// the next box hides behind the sweeps of the current one: request() loads this thread's (at most
+// two) elements of the sub-box into registers, run() stages them and does the x, y and z passes.
+struct CentredBox {
+    int sx, nx, sy, ny, sz, nz, fx0, fy0, fz0, clx, cly, clz, ncx, ncy, ncz;
+    const double* cpad;
+
+    __device__ __forceinline__ void set(const BlockInfo& bi, const double* cpad_, int sx_, int nx_, int sy_, int ny_, int sz_, int nz_)
+    {
+        cpad = cpad_; sx = sx_; nx = nx_; sy = sy_; ny = ny_; sz = sz_; nz = nz_;
+        fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
+        fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
+        fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
+        clx = (fx0 >> 1) - 2; ncx = ((fx0 + nx - 1) >> 1) + 3 - clx + 1;
+        cly = (fy0 >> 1) - 2; ncy = ((fy0 + ny - 1) >> 1) + 3 - cly + 1;
+        clz = (fz0 >> 1) - 2; ncz = ((fz0 + nz - 1) >> 1) + 3 - clz + 1;
     }
-    __syncthreads();
-    for (int q = tid; q < ncz * ncy * nx; q += NTHREADS) {       // x pass, item (row = cz*ncy + cy, tx)
-        const int row = div_by(q, mx), tx = q - row * nx;
-        T1[q] = centred_line(&C[row * ncx], 1, fx0 + tx, clx, bi.lag);
+    __device__ __forceinline__ void request(double (&c)[2], int tid) const
+    {
+        const uint32_t mcx = div_magic(ncx), mcxy = div_magic(ncx * ncy);
+        const int n = ncz * ncy * ncx;                           // at most 847
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int q = tid + m * NTHREADS;
+            if (q < n) {
+                const int cz = div_by(q, mcxy), r = q - cz * ncx * ncy, cy = div_by(r, mcx), cx = r - cy * ncx;
+                c[m] = cpad[((clz + cz + PAD) * NP + (cly + cy + PAD)) * NP + (clx + cx + PAD)];
+            }
+        }
     }
-    __syncthreads();
-    for (int q = tid; q < ncz * ny * nx; q += NTHREADS) {        // y pass, item (cz, ty, tx)
-        const int cz = div_by(q, mxy), r = q - cz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
-        T2[q] = centred_line(&T1[cz * ncy * nx + tx], nx, fy0 + ty, cly, bi.lag);
+    // stores the requested elements; the caller may issue the next request() between stage() and sweep()
+    __device__ __forceinline__ void stage(double* scratch, const double (&c)[2], int tid) const
+    {
+        double* C = scratch + ncz * ncy * nx;                    // behind the x-pass results; reused by the y pass
+        const int n = ncz * ncy * ncx;
+        __syncthreads();                                         // everybody is done with the staging arrays
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+            if (tid + m * NTHREADS < n) C[tid + m * NTHREADS] = c[m];
+        __syncthreads();
     }
-    __syncthreads();
-    for (int q = tid; q < nz * ny * nx; q += NTHREADS) {         // z pass, into the tile
-        const int tz = div_by(q, mxy), r = q - tz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
-        tile[tidx(sz + tz, sy + ty, sx + tx)] = centred_line(&T2[r], nx * ny, fz0 + tz, clz, bi.lag);
+    __device__ __forceinline__ void sweep(double* tile, double* scratch, const BlockInfo& bi, int tid) const
+    {
+        double* T1 = scratch;                    // after the x pass  [cz][cy][tx]
+        double* T2 = T1 + ncz * ncy * nx;        // after the y pass  [cz][ty][tx]
+        const double* C = T2;                    // the coarse sub-box [cz][cy][cx]: dead once the x pass is done
+        const uint32_t mx = div_magic(nx), mxy = div_magic(nx * ny);
+        for (int q = tid; q < ncz * ncy * nx; q += NTHREADS) {       // x pass, item (row = cz*ncy + cy, tx)
+            const int row = div_by(q, mx), tx = q - row * nx;
+            T1[q] = centred_line(&C[row * ncx], 1, fx0 + tx, clx, bi.lag);
+        }
+        __syncthreads();
+        for (int q = tid; q < ncz * ny * nx; q += NTHREADS) {        // y pass, item (cz, ty, tx)
+            const int cz = div_by(q, mxy), r = q - cz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
+            T2[q] = centred_line(&T1[cz * ncy * nx + tx], nx, fy0 + ty, cly, bi.lag);
+        }
+        __syncthreads();
+        for (int q = tid; q < nz * ny * nx; q += NTHREADS) {         // z pass, into the tile
+            const int tz = div_by(q, mxy), r = q - tz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
+            tile[tidx(sz + tz, sy + ty, sx + tx)] = centred_line(&T2[r], nx * ny, fz0 + tz, clz, bi.lag);
+        }
     }
-}
+};
 
 // every coarser source leaf of the block, one after the other; pbase = one variable's compact array of
-// padded source leaves
+// padded source leaves (or, with by_id, the padded array of all blocks)
+template <bool BY_ID = false>
 __device__ __forceinline__ void interp_boxes_centred(double* tile, double* scratch, const BlockInfo& bi,
                                                      const double* __restrict__ pbase, int tid)
 {
     const BoxPlan& bp = bi.box;
     const int ns = bp.rbeg[bp.nround];
+    auto box = [&](CentredBox& cb, int s) {
+        const int64_t src = BY_ID ? bi.cs[2 * s] : bi.slot[s];
+        cb.set(bi, pbase + src * PBLK, bp.sx[s], bp.nx[s], bp.sy[s], bp.ny[s], bp.sz[s], bp.nz[s]);
+    };
+    if (ns == 0) return;
+    CentredBox cur, nxt;
+    double c[2];
+    box(cur, 0);
+    cur.request(c, tid);
 #pragma unroll 1
-    for (int s = 0; s < ns; ++s)
-        interp_box_centred(tile, scratch, bi, pbase + (int64_t)bi.slot[s] * PBLK, bp.sx[s], bp.nx[s], bp.sy[s], bp.ny[s],
-                           bp.sz[s], bp.nz[s], tid);
+    for (int s = 0; s < ns; ++s) {
+        cur.stage(scratch, c, tid);
+        if (s + 1 < ns) { box(nxt, s + 1); nxt.request(c, tid); }
+        cur.sweep(tile, scratch, bi, tid);
+        cur = nxt;
+    }
 }
 // the same where only the face slabs of the tile are read: one 3 x 8 x 8 box per coarser face
 __device__ __forceinline__ void interp_faces_centred(double* tile, double* scratch, const BlockInfo& bi,
                                                      const double* __restrict__ pbase, int tid)
 {
     const int n = bi.cs[16];
+    auto box = [&](CentredBox& cb, int q) {
+        const int face = bi.cs[17 + 2 * q], ax = face >> 1, s0 = (face & 1) ? PAD + NPT : 0;
+        cb.set(bi, pbase + (int64_t)bi.slot[bi.box.face_src[q]] * PBLK, ax == 0 ? s0 : PAD, ax == 0 ? PAD : NPT,
+               ax == 1 ? s0 : PAD, ax == 1 ? PAD : NPT, ax == 2 ? s0 : PAD, ax == 2 ? PAD : NPT);
+    };
+    if (n == 0) return;
+    CentredBox cur, nxt;
+    double c[2];
+    box(cur, 0);
+    cur.request(c, tid);
 #pragma unroll 1
     for (int q = 0; q < n; ++q) {
-        const int face = bi.cs[17 + 2 * q], ax = face >> 1, s0 = (face & 1) ? PAD + NPT : 0;
-        const int sx = ax == 0 ? s0 : PAD, sy = ax == 1 ? s0 : PAD, sz = ax == 2 ? s0 : PAD;
-        const int nx = ax == 0 ? PAD : NPT, ny = ax == 1 ? PAD : NPT, nz = ax == 2 ? PAD : NPT;
-        interp_box_centred(tile, scratch, bi, pbase + (int64_t)bi.slot[bi.box.face_src[q]] * PBLK, sx, nx, sy, ny, sz, nz, tid);
+        cur.stage(scratch, c, tid);
+        if (q + 1 < n) { box(nxt, q + 1); nxt.request(c, tid); }
+        cur.sweep(tile, scratch, bi, tid);
+        cur = nxt;
     }
 }
 
@@ -970,13 +1022,8 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const
     double cv[CPRE];
     commit<false, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, zipped, tid);   // stores only
     __syncthreads();                                 // the box plan is complete
-    const int ns = bi.box.rbeg[bi.box.nround];
-#pragma unroll 1
-    for (int s = 0; s < ns; ++s) {
-        const int64_t src = SOURCES ? bi.slot[s] : bi.cs[2 * s];
-        interp_box_centred(tile, scratch, bi, padded + (v * nout + src) * PBLK, bi.box.sx[s], bi.box.nx[s], bi.box.sy[s],
-                           bi.box.ny[s], bi.box.sz[s], bi.box.nz[s], tid);
-    }
+    if (SOURCES) interp_boxes_centred<false>(tile, scratch, bi, padded + v * nout * PBLK, tid);
+    else interp_boxes_centred<true>(tile, scratch, bi, padded + v * nout * PBLK, tid);
     __syncthreads();
     double* out = padded + (v * nout + (SOURCES ? (int64_t)tr.src_slot[b] : b)) * PBLK;
 #pragma unroll

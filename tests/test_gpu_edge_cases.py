@@ -112,3 +112,48 @@ def test_burgers_many_steps_towards_the_shock(orc, dev):  # noqa: F811
         tg.rk_step(2, ud, dt, ws, sigma=0.05)
         ref = to.rk4_step(2, ref, dt, sigma=0.05)
     assert_close(ud.cpu().numpy(), ref, "3 Burgers steps")
+
+
+def corner_params(lmax=6):
+    """refinement centred next to the corner of the periodic cube: the level jumps sit on the wrap"""
+    q = 1 << 20
+    pts = np.array([[40, q - 30, 17], [q - 5, 9, q - 1]], dtype=np.uint32)
+    return dict(lmin=3, lmax=lmax, pts_q20=pts, radius_q20=np.array([90000, 60000, 40000][:lmax - 3], np.uint32))
+
+
+def test_level_jumps_across_the_periodic_wrap(orc, dev):  # noqa: F811
+    p = corner_params()
+    to, tg = orc.Tree.build(**p), octfd.Tree.build(**p)
+    assert (to.leaves == tg.leaves).all() and (to.ghost_table() == tg.ghost_table()).all()
+    lv = to.leaves.astype(np.int64)
+    fine = lv[:, 0] == 6
+    edge = np.zeros(to.n, dtype=bool)
+    for c in (1, 2, 3):
+        edge |= (lv[:, c] == 0) | (lv[:, c] == (1 << lv[:, 0]) - 1)
+    assert (fine & edge).sum() > 50                   # finest blocks that touch the wrap
+    rng = np.random.default_rng(8)
+    u = rng.standard_normal((24, to.n, 8, 8, 8))
+    ud = torch.from_numpy(u).to(dev)
+    # ghost fill, both rules
+    for name, fo, fg in (("unzip", to.unzip, tg.unzip), ("unzip_centred", to.unzip_centred, tg.unzip_centred)):
+        pad = dev_empty((2, to.n, 14, 14, 14), dev)
+        fg(ud[:2].contiguous(), pad)
+        assert_close(pad.cpu().numpy(), fo(u[:2]), "%s across the wrap" % name)
+    # the 24-field right-hand side and one step with each rule
+    out = dev_empty((24, to.n, 8, 8, 8), dev)
+    tg.rhs_eval_zipped(3, ud, out, sigma=0.4)
+    assert_close(out.cpu().numpy(), to.F(3, u, sigma=0.4), "SYN24 right-hand side across the wrap")
+    us = 0.01 * u[:2]
+    dt = sd.time_step(6)
+    for name, so, sg_, wsb in (("rk_step", to.rk4_step, tg.rk_step, tg.rk_workspace_bytes(1)),
+                               ("rk_step_centred", to.rk4_step_centred, tg.rk_step_centred, tg.rk_centred_workspace_bytes(1))):
+        x = torch.from_numpy(us).to(dev).clone()
+        sg_(1, x, dt, torch.empty(wsb // 8, dtype=torch.float64, device=dev), sigma=0.4)
+        assert_close(x.cpu().numpy(), so(1, us, dt, 0.4), "%s across the wrap" % name)
+    # regrid to centres moved further round the corner
+    p2 = dict(p, pts_q20=(p["pts_q20"].astype(np.int64) + np.array([[6000, 6000, -5000], [-7000, 3000, 4000]])) % (1 << 20))
+    p2["pts_q20"] = p2["pts_q20"].astype(np.uint32)
+    to2, tg2 = orc.Tree.build(**p2), octfd.Tree.build(**p2)
+    got = dev_empty((2, to2.n, 8, 8, 8), dev)
+    octfd.Transfer(tg, tg2).apply(ud[:2].contiguous(), got)
+    assert_close(got.cpu().numpy(), orc.transfer(to, to2, u[:2]), "regrid across the wrap")

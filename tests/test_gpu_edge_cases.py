@@ -157,3 +157,29 @@ def test_level_jumps_across_the_periodic_wrap(orc, dev):  # noqa: F811
     got = dev_empty((2, to2.n, 8, 8, 8), dev)
     octfd.Transfer(tg, tg2).apply(ud[:2].contiguous(), got)
     assert_close(got.cpu().numpy(), orc.transfer(to, to2, u[:2]), "regrid across the wrap")
+
+
+def test_thirteen_levels(orc, dev):  # noqa: F811
+    """levels 3..15 around one point: grid spacings from 2^-6 down to 2^-18 in one tree"""
+    lmax = 15
+    rad = np.array([int(1.6 * 2 ** (20 - l)) for l in range(3, lmax)], np.uint32)
+    p = dict(lmin=3, lmax=lmax, pts_q20=np.array([[333333, 777777, 555555]], np.uint32), radius_q20=rad)
+    to, tg = orc.Tree.build(**p), octfd.Tree.build(**p)
+    assert (to.leaves == tg.leaves).all() and (to.ghost_table() == tg.ghost_table()).all()
+    assert sorted(set(to.leaves[:, 0])) == list(range(3, lmax + 1))
+    u = np.random.default_rng(12).standard_normal((24, to.n, 8, 8, 8))
+    ud = torch.from_numpy(u).to(dev)
+    out = dev_empty((24, to.n, 8, 8, 8), dev)
+    tg.rhs_eval_zipped(3, ud, out, sigma=0.4)
+    assert_close(out.cpu().numpy(), to.F(3, u, sigma=0.4), "SYN24 right-hand side, levels 3..15")
+    us = u[:2].copy()
+    dt = sd.time_step(lmax)
+    x = torch.from_numpy(us).to(dev).clone()
+    tg.rk_step_centred(1, x, dt, torch.empty(tg.rk_centred_workspace_bytes(1) // 8, dtype=torch.float64, device=dev), sigma=0.4)
+    assert_close(x.cpu().numpy(), to.rk4_step_centred(1, us, dt, 0.4), "rk_step_centred, levels 3..15")
+    # coarsen everything back to level 3: injection through up to twelve levels
+    t3o, t3g = uniform(orc, 3)
+    got = dev_empty((2, t3g.n, 8, 8, 8), dev)
+    octfd.Transfer(tg, t3g).apply(ud[:2].contiguous(), got)
+    want = orc.transfer(to, t3o, u[:2])
+    assert (got.cpu().numpy() == want).all()

@@ -25,6 +25,8 @@
  *                          padded  [var][block][kk][jj][ii]  14*14*14, (ii,jj,kk) = (i,j,k)+3
  *     blocks are stored in Morton order of their anchors (x least significant bit).
  *   - input and output arrays must not overlap, except u in rk_step.
+ *   - device calls accept trees of fewer than 2^20 blocks (OT_E_UNSUPPORTED otherwise); the host
+ *     calls have no such limit.
  */
 #ifndef OCTFD_H
 #define OCTFD_H

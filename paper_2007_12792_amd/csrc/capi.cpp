@@ -54,14 +54,14 @@ int same_device(int device)
 int ensure_device(ot_tree* t)
 {
     if (t->device >= 0) return same_device(t->device);
+    // kernels address one variable's zipped array with 32-bit byte offsets
+    if (t->host.leaves.size() >= (size_t(1) << 20)) return OT_E_UNSUPPORTED;
     int ndev = 0;
     hipError_t e = hipGetDeviceCount(&ndev);
     if (e != hipSuccess) return hip_fail(e);
     if (ndev <= 0) return OT_E_NODEVICE;
     int dev = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e);
-    // kernels address one variable's zipped array with 32-bit byte offsets
-    if (t->host.leaves.size() >= (size_t(1) << 20)) return OT_E_UNSUPPORTED;
     const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
     // one allocation for all tables, each part 256-byte aligned
     const HostTree& h = t->host;

@@ -193,3 +193,12 @@ def test_regrid_plan_refuses_two_level_refinement_and_bad_arguments():
     assert L.regrid_plan(None, coarse._h, C.byref(h)) == octfd.OT_E_BADARG
     assert L.regrid_transfer(None, 1, None, None, None) == octfd.OT_E_BADARG
     assert L.regrid_free(None) == octfd.OT_OK
+
+
+def test_trees_of_a_million_blocks_are_refused_by_the_device_calls():
+    # 2^21 leaves: the host tables exist, but the kernels' 32-bit offsets would not reach
+    t = octfd.Tree.build(7, 7, np.zeros((1, 3), np.uint32), np.zeros(0, np.uint32))
+    assert t.n == 1 << 21
+    with pytest.raises(octfd.OctfdError) as e:
+        t.upload()
+    assert e.value.status == octfd.OT_E_UNSUPPORTED

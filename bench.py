@@ -204,7 +204,8 @@ def main():
                    % (args.config, cfg["kind"], cfg["lmin"], cfg["lmax"], nb, V, sg, args.seed),
                    "n_blocks": nb, "n_vars": V, "rhs_evals_per_step": 4,
                    "zipped_state_GB": nb * 512 * V * 8 / 1e9, "tree_build_s": t_build,
-                   "ms_per_step_all": per_step_ms, "wall_s_timed_region": wall},
+                   "ms_per_step_all": per_step_ms, "ms_per_step_median": float(np.median(per_step_ms)),
+                   "ms_per_step_min": float(min(per_step_ms)), "wall_s_timed_region": wall},
         "roofline": {"bound": "hbm", "kernel": "k_rhs<%s, zipped in, RK-stage epilogue> (4 launches per step)" % cfg["kind"],
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "launch_ms": launch_ms, "algorithmic_bytes_per_launch": bytes_per_launch,

@@ -105,6 +105,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="C5", help="workload name from synthdata.CONFIGS (default: the headline one)")
     ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--region", choices=("auto", "rk", "rhs"), default="auto",
+                    help="timed step: one RK4 step (rk) or one fused right-hand-side evaluation (rhs); auto = what the workload names")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-blocks", type=int, default=0, help="0 = every block of the tree")
     ap.add_argument("--other-kernels", action="store_true",
@@ -141,24 +143,35 @@ def main():
     if args.other_kernels:
         other_kernels(args, cfg, kind, dev)
         return
-    if octfd.nvar_in(kind) != octfd.nvar_out(kind):
-        sys.exit("bench.py: the timed step is rk_step; choose a workload whose kind can be stepped")
+    # the step: one RK4 step, or, for the workloads whose timed region is a single evaluation (and for kinds
+    # that cannot be stepped), one fused right-hand-side evaluation
+    single_rhs = args.region == "rhs" or (args.region == "auto" and (args.config in ("C1", "C2", "C4")
+                                                                     or octfd.nvar_in(kind) != octfd.nvar_out(kind)))
+    if not single_rhs and octfd.nvar_in(kind) != octfd.nvar_out(kind):
+        sys.exit("bench.py: --region rk needs a workload whose kind can be stepped")
     p = sd.tree_params(args.config, args.seed)
     t0 = time.time()
     tree = octfd.Tree.build(**p)
     t_build = time.time() - t0
     leaves = tree.leaves
-    nb, V = tree.n, octfd.nvar_in(kind)
+    nb, V = tree.n, octfd.nvar_out(kind)
     u = sd.make_fields(args.config, leaves, args.seed, device=dev)
     u0 = u.clone()
-    ws = torch.empty(tree.rk_workspace_bytes(kind) // 8, dtype=torch.float64, device=dev)
-    dt, sg = sd.time_step(cfg["lmax"]), sd.KO_SIGMA
+    dt, sg = sd.time_step(cfg["lmax"]), (0.0 if cfg["kind"] == "DERIVS" else sd.KO_SIGMA)
     tree.upload()
-
     stream = torch.cuda.current_stream()
+    if single_rhs:
+        kout = torch.empty((V, nb, 8, 8, 8), dtype=torch.float64, device=dev)
+        step = lambda: tree.rhs_eval_zipped(kind, u, kout, sigma=sg, stream=stream)
+        launches_per_step, stage_bytes = 1, (16.0,) if octfd.nvar_in(kind) == V else (8.0 * octfd.nvar_in(kind) / V + 8.0,)
+    else:
+        ws = torch.empty(tree.rk_workspace_bytes(kind) // 8, dtype=torch.float64, device=dev)
+        step = lambda: tree.rk_step(kind, u, dt, ws, sigma=sg, stream=stream)
+        launches_per_step, stage_bytes = 4, STAGE_BYTES
+
     for _ in range(args.warmup):
         u.copy_(u0)
-        tree.rk_step(kind, u, dt, ws, sigma=sg, stream=stream)
+        step()
     u.copy_(u0)
     # the launches go to `stream`; the events are recorded on the same stream
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
@@ -166,14 +179,14 @@ def main():
     w0 = time.perf_counter()
     ev[0].record(stream)
     for i in range(args.steps):
-        tree.rk_step(kind, u, dt, ws, sigma=sg, stream=stream)
+        step()
         ev[i + 1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - w0
     per_step_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
     total_ms = ev[0].elapsed_time(ev[-1])
     ms_per_step = total_ms / args.steps
-    updates_per_step = nb * 512 * V * 4
+    updates_per_step = nb * 512 * V * launches_per_step
     value = updates_per_step / (ms_per_step * 1e-3)
 
     # what a plain device copy reaches on this GPU: the practical ceiling under the published HBM peak
@@ -192,28 +205,30 @@ def main():
 
     # dominant kernel = the fused right-hand-side/stage kernel, launched 4 times per step and nothing else
     # runs in the timed region: average launch duration = region / (4 * steps)
-    launch_ms = total_ms / (4 * args.steps)
-    bytes_per_launch = sum(STAGE_BYTES) / 4.0 * nb * 512 * V
+    launch_ms = total_ms / (launches_per_step * args.steps)
+    bytes_per_launch = sum(stage_bytes) / len(stage_bytes) * nb * 512 * V
     achieved = bytes_per_launch / (launch_ms * 1e-3) / 1e9
     out = {
         "metric": "block-point RHS updates/sec (fp64, per var) + achieved HBM GB/s, 1 GPU",
         "value": value, "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
-        "config": {"workload": "%s: %s RK4 step, 2:1-balanced octree levels %d-%d, %d blocks of 8^3 (pad 3), %d fields, KO sigma %.1f, seed %d"
-                   % (args.config, cfg["kind"], cfg["lmin"], cfg["lmax"], nb, V, sg, args.seed),
-                   "n_blocks": nb, "n_vars": V, "rhs_evals_per_step": 4,
+        "config": {"workload": "%s: %s %s, 2:1-balanced octree levels %d-%d, %d blocks of 8^3 (pad 3), %d fields, KO sigma %.1f, seed %d"
+                   % (args.config, cfg["kind"], "fused right-hand-side evaluation" if single_rhs else "RK4 step", cfg["lmin"], cfg["lmax"],
+                      nb, V, sg, args.seed),
+                   "n_blocks": nb, "n_vars": V, "rhs_evals_per_step": launches_per_step,
                    "zipped_state_GB": nb * 512 * V * 8 / 1e9, "tree_build_s": t_build,
                    "ms_per_step_all": per_step_ms, "ms_per_step_median": float(np.median(per_step_ms)),
                    "ms_per_step_min": float(min(per_step_ms)), "wall_s_timed_region": wall},
-        "roofline": {"bound": "hbm", "kernel": "k_rhs<%s, zipped in, RK-stage epilogue> (4 launches per step)" % cfg["kind"],
+        "roofline": {"bound": "hbm", "kernel": "k_rhs<%s, zipped in, %s> (%d per step)"
+                               % (cfg["kind"], "plain output" if single_rhs else "RK-stage epilogue", launches_per_step),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "launch_ms": launch_ms, "algorithmic_bytes_per_launch": bytes_per_launch,
-                     "traffic": measured_traffic(args.config, nb),
+                     "traffic": None if single_rhs else measured_traffic(args.config, nb),
                      # the same launch time against three byte counts: what the method must move at the very
                      # least (8 B in + 8 B out per update), what this pipeline moves by construction
                      # (= achieved), and what the counters saw (= traffic)
-                     "compulsory_GBs": 16.0 * nb * 512 * V / (launch_ms * 1e-3) / 1e9,
+                     "compulsory_GBs": (8.0 * octfd.nvar_in(kind) + 8.0 * V) * nb * 512 / (launch_ms * 1e-3) / 1e9,
                      "device_copy_GBs": copy_gbs},
     }
     tr = out["roofline"]["traffic"]

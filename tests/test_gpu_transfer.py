@@ -103,3 +103,32 @@ def test_step_regrid_step_matches_the_oracle(orc, dev):
     got = ub.cpu().numpy()
     print("step, regrid %d -> %d blocks, step: %d of %d values differ" % (oa.n, ob.n, int((got != want).sum()), got.size), flush=True)
     assert (np.abs(got - want) <= RTOL * np.abs(want) + ATOL).all()
+
+
+def test_adaptive_run_in_miniature_with_the_centred_rule(orc, dev):
+    """three cycles of (two centred RK4 steps of the wave system, regrid to centres moved along the
+    orbit, transfer); the whole sequence through the library and through the oracle"""
+    kind = octfd.WAVE
+    dt, sg = sd.time_step(5), sd.KO_SIGMA
+    phases = [0.0, 0.07, 0.14, 0.21]
+    trees_o = [orc.Tree.build(**sd.tree_params("T4", 1, phase=ph)) for ph in phases]
+    trees_g = [octfd.Tree.build(**sd.tree_params("T4", 1, phase=ph)) for ph in phases]
+    x, y, z = sd.node_coords(trees_o[0].leaves)
+    u = torch.stack([torch.exp(-((x - 0.5) ** 2 + (y - 0.5) ** 2 + (z - 0.5) ** 2) / 0.02), torch.zeros_like(x)]).contiguous()
+    want = u.numpy()
+    got = u.to(dev)
+    for c in range(3):
+        to, tg = trees_o[c], trees_g[c]
+        ws = torch.empty(tg.rk_centred_workspace_bytes(kind) // 8, dtype=torch.float64, device=dev)
+        for _ in range(2):
+            want = to.rk4_step_centred(kind, want, dt, sg)
+            tg.rk_step_centred(kind, got, dt, ws, sigma=sg)
+        want = orc.transfer(to, trees_o[c + 1], want)
+        nxt = torch.full((2, trees_g[c + 1].n, 8, 8, 8), float("nan"), dtype=torch.float64, device=dev)
+        octfd.Transfer(tg, trees_g[c + 1]).apply(got, nxt)
+        got = nxt
+    torch.cuda.synchronize()
+    g = got.cpu().numpy()
+    print("adaptive run: %d of %d values differ, max |u| %.3f" % (int((g != want).sum()), g.size, np.abs(g[0]).max()), flush=True)
+    assert (np.abs(g - want) <= RTOL * np.abs(want) + ATOL).all()
+    assert np.abs(g[0]).max() < 1.5

@@ -965,33 +965,48 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, con
     __shared__ double tile[TILE];
     __shared__ double scratch[SCRATCH];
     __shared__ BlockInfo bi;
-    __shared__ uint32_t plan_src[PLAN_FULL * NTHREADS];
     const int tid = threadIdx.x;
-    // Workgroup v + nvar b: with the workgroups dealt to the eight XCDs in turn, an XCD sees a fixed
-    // subset of the variables (all of them when nvar is a multiple of 8: v mod 8) for consecutive
-    // blocks one after the other, so a ghost row it fetches was, or soon will be, an interior row of
-    // a block it handles for the same variable and is served by its L2.  (Measured on the
-    // 102,075-block tree with 24 variables: 22 GB fetched per call against 77 GB with the blocks of
-    // one variable launched together.)
-    const int64_t b = blockIdx.x / nvar, v = blockIdx.x - b * nvar, nb = tr.nb;
+    // Workgroup r + G b fills the padded blocks of variables r, r + G, r + 2G, ... of block b, G =
+    // min(8, nvar).  With the workgroups dealt to the eight XCDs in turn, an XCD sees a fixed subset of
+    // the variables for consecutive blocks one after the other, so a ghost row it fetches was, or soon
+    // will be, an interior row of a block it handles for the same variable and is served by its L2
+    // (102,075-block tree, 24 variables: 22 GB fetched per call against 77 GB with the blocks of one
+    // variable launched together).  The fill plan is built once per workgroup and kept in registers.
+    const int stride = nvar < NXCD ? nvar : NXCD;
+    const int64_t b = blockIdx.x / stride, nb = tr.nb;
+    const int v0 = (int)(blockIdx.x - b * stride);
     load_block_info(bi, tr, b, tid);
     __syncthreads();
     if (tid == 0) make_box_plan(bi);
     FillPlan<PLAN_FULL> fp;
-    fp.src = plan_src;
+    fp.src = reinterpret_cast<uint32_t*>(scratch);   // the staging area is free until the first interpolation
     make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);
-    double pv[PLAN_FULL];
-    prefetch<PLAN_FULL, PLAN_FULL>(pv, fp, zipped + v * nb * BLK, tid);
-    double cv[CPRE];
-    __syncthreads();                                 // the box plan is complete
-    commit<true, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, zipped + v * nb * BLK, tid);
-    __syncthreads();
-    double* out = padded + (v * nb + b) * PBLK;
+    uint32_t off[PLAN_FULL];
+    int from[PLAN_FULL];
 #pragma unroll
     for (int m = 0; m < PLAN_FULL; ++m) {
-        const int p = tid + m * NTHREADS;
+        off[m] = fp.src[m * NTHREADS + tid];             // this thread's own entries: no barrier needed
+        const int p = min(tid + m * NTHREADS, PBLK - 1);
         const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
-        if (p < PBLK) out[p] = tile[tidx(kk, jj, ii)];
+        from[m] = tidx(kk, jj, ii);                      // where this thread's output elements sit in the tile
+    }
+    double cv[CPRE];
+    __syncthreads();                                 // the box plan is complete; the plan has left the staging area
+#pragma unroll 1
+    for (int v = v0; v < nvar; v += stride) {
+        const double* base = zipped + (int64_t)v * nb * BLK;
+        double pv[PLAN_FULL];
+#pragma unroll
+        for (int m = 0; m < PLAN_FULL; ++m) pv[m] = ldg(base, off[m]);
+        commit<true, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, base, tid);
+        __syncthreads();
+        double* out = padded + ((int64_t)v * nb + b) * PBLK;
+#pragma unroll
+        for (int m = 0; m < PLAN_FULL; ++m) {
+            const int p = tid + m * NTHREADS;
+            if (p < PBLK) out[p] = tile[from[m]];
+        }
+        __syncthreads();                             // the tile and the staging area are free again
     }
 }
 
@@ -1006,31 +1021,48 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const
     __shared__ double tile[TILE];
     __shared__ double scratch[CENTRED_STAGING];
     __shared__ BlockInfo bi;
-    __shared__ uint32_t plan_src[PLAN_FULL * NTHREADS];
+    static_assert(PLAN_FULL * NTHREADS * sizeof(uint32_t) <= CENTRED_STAGING * sizeof(double), "the plan is built in the staging area");
     const int tid = threadIdx.x;
-    // variable fastest in the launch order, as in k_unzip
-    const int64_t q = blockIdx.x / nvar, v = blockIdx.x - q * nvar, b = blocks[q], nb = tr.nb;
+    // workgroup r + G q: variables r, r + G, ... of the q-th block of the list, G = min(8, nvar), as in k_unzip
+    const int stride = nvar < NXCD ? nvar : NXCD;
+    const int64_t q = blockIdx.x / stride, b = blocks[q], nb = tr.nb;
+    const int v0 = (int)(blockIdx.x - q * stride);
     const int64_t nout = SOURCES ? tr.n_src : nb;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
     if (tid == 0) make_box_plan(bi);
     FillPlan<PLAN_FULL> fp;
-    fp.src = plan_src;
+    fp.src = reinterpret_cast<uint32_t*>(scratch);   // the staging area is free until the first interpolation
     make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);
-    double pv[PLAN_FULL];
-    prefetch<PLAN_FULL, PLAN_FULL>(pv, fp, zipped + v * nb * BLK, tid);
-    double cv[CPRE];
-    commit<false, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, zipped, tid);   // stores only
-    __syncthreads();                                 // the box plan is complete
-    if (SOURCES) interp_boxes_centred<false>(tile, scratch, bi, padded + v * nout * PBLK, tid);
-    else interp_boxes_centred<true>(tile, scratch, bi, padded + v * nout * PBLK, tid);
-    __syncthreads();
-    double* out = padded + (v * nout + (SOURCES ? (int64_t)tr.src_slot[b] : b)) * PBLK;
+    uint32_t off[PLAN_FULL];
+    int from[PLAN_FULL];
 #pragma unroll
     for (int m = 0; m < PLAN_FULL; ++m) {
-        const int p = tid + m * NTHREADS;
+        off[m] = fp.src[m * NTHREADS + tid];
+        const int p = min(tid + m * NTHREADS, PBLK - 1);
         const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
-        if (p < PBLK) out[p] = tile[tidx(kk, jj, ii)];
+        from[m] = tidx(kk, jj, ii);
+    }
+    double cv[CPRE];
+    const int64_t oslot = SOURCES ? (int64_t)tr.src_slot[b] : b;
+    __syncthreads();                                 // the box plan is complete; the plan has left the staging area
+#pragma unroll 1
+    for (int v = v0; v < nvar; v += stride) {
+        const double* base = zipped + (int64_t)v * nb * BLK;
+        double pv[PLAN_FULL];
+#pragma unroll
+        for (int m = 0; m < PLAN_FULL; ++m) pv[m] = ldg(base, off[m]);
+        commit<false, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, base, tid);   // stores only
+        if (SOURCES) interp_boxes_centred<false>(tile, scratch, bi, padded + (int64_t)v * nout * PBLK, tid);
+        else interp_boxes_centred<true>(tile, scratch, bi, padded + (int64_t)v * nout * PBLK, tid);
+        __syncthreads();
+        double* out = padded + ((int64_t)v * nout + oslot) * PBLK;
+#pragma unroll
+        for (int m = 0; m < PLAN_FULL; ++m) {
+            const int p = tid + m * NTHREADS;
+            if (p < PBLK) out[p] = tile[from[m]];
+        }
+        __syncthreads();                             // the tile and the staging area are free again
     }
 }
 
@@ -1087,7 +1119,7 @@ hipError_t launch_kind(const DeviceTree& t, bool zin, bool centred, Epilogue ep,
 hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, double* padded, hipStream_t s)
 {
     if (t.nb <= 0 || nvar <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_unzip, dim3((unsigned)(t.nb * nvar)), dim3(NTHREADS), 0, s, t, nvar, zipped, padded);
+    hipLaunchKernelGGL(k_unzip, dim3((unsigned)(t.nb * (nvar < NXCD ? nvar : NXCD))), dim3(NTHREADS), 0, s, t, nvar, zipped, padded);
     return hipGetLastError();
 }
 
@@ -1099,10 +1131,10 @@ hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start,
         const int64_t n = level_start[l + 1] - level_start[l];
         if (n <= 0) continue;
         if (sources_only)
-            hipLaunchKernelGGL(k_unzip_centred<true>, dim3((unsigned)(n * nvar)), dim3(NTHREADS), 0, s, t,
+            hipLaunchKernelGGL(k_unzip_centred<true>, dim3((unsigned)(n * (nvar < NXCD ? nvar : NXCD))), dim3(NTHREADS), 0, s, t,
                                t.src_by_level + level_start[l], nvar, zipped, padded);
         else
-            hipLaunchKernelGGL(k_unzip_centred<false>, dim3((unsigned)(n * nvar)), dim3(NTHREADS), 0, s, t,
+            hipLaunchKernelGGL(k_unzip_centred<false>, dim3((unsigned)(n * (nvar < NXCD ? nvar : NXCD))), dim3(NTHREADS), 0, s, t,
                                t.by_level + level_start[l], nvar, zipped, padded);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -202,3 +202,15 @@ def test_trees_of_a_million_blocks_are_refused_by_the_device_calls():
     with pytest.raises(octfd.OctfdError) as e:
         t.upload()
     assert e.value.status == octfd.OT_E_UNSUPPORTED
+
+
+def test_bench_refuses_more_than_one_gpu_and_a_missing_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr
+    import torch
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "1"], capture_output=True, text=True, timeout=300)
+        assert r.returncode != 0 and "no GPU" in r.stderr and "{" not in r.stdout

@@ -183,3 +183,39 @@ def test_thirteen_levels(orc, dev):  # noqa: F811
     octfd.Transfer(tg, t3g).apply(ud[:2].contiguous(), got)
     want = orc.transfer(to, t3o, u[:2])
     assert (got.cpu().numpy() == want).all()
+
+
+@pytest.mark.parametrize("name,kind,nsteps", [("T3", 1, 3), ("T4", 3, 2)])
+def test_rk_step_can_be_captured_in_a_graph_and_replayed(dev, name, kind, nsteps):  # noqa: F811
+    """After octree_upload the device calls only enqueue kernels: no allocation, no synchronisation,
+    no memset.  A step captured in a graph must replay to the same bits as eager steps, every time.
+    (Two steps only for the 24-field system, whose values overflow after a few steps at this dt.)"""
+    tg = octfd.Tree.build(**sd.tree_params(name, 1))
+    tg.upload()
+    u0 = sd.make_fields(name, tg.leaves, 1, device=dev)
+    dt = sd.time_step(5)
+    ws = torch.empty(tg.rk_workspace_bytes(kind) // 8, dtype=torch.float64, device=dev)
+    eager = []
+    u = u0.clone()
+    for _ in range(nsteps):
+        tg.rk_step(kind, u, dt, ws, sigma=0.4)
+        eager.append(u.clone())
+    torch.cuda.synchronize()
+    assert torch.isfinite(eager[-1]).all()
+    ug = u0.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        tg.rk_step(kind, ug, dt, ws, sigma=0.4)       # warm-up on a side stream, as graph capture asks
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    ug.copy_(u0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        tg.rk_step(kind, ug, dt, ws, sigma=0.4)       # stream=None -> the current (capturing) stream
+    ug.copy_(u0)
+    for n in range(nsteps):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ug, eager[n]), "replay %d" % n
+        assert np.isfinite((eager[n] * 0.5).sum().item())   # eager work and a synchronisation between replays

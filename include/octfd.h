@@ -134,7 +134,8 @@ int unzip(ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev,
 int rhs_eval(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
              const double *padded_dev, double *rhs_padded_dev, void *hip_stream);
 
-/* zip: padded_dev [nvar][nb][14^3] -> zipped_dev [nvar][nb][8^3]; drops the ghost layers. */
+/* zip: padded_dev [nvar][nb][14^3] -> zipped_dev [nvar][nb][8^3]; drops the ghost layers.
+ * OT_E_UNSUPPORTED when nb * nvar exceeds 2^31 - 1 (one workgroup per block and variable). */
 int zip(ot_tree *tree, int nvar, const double *padded_dev, double *zipped_dev, void *hip_stream);
 
 /* The three calls above fused: zipped in, zipped right-hand side out, no padded array in memory.

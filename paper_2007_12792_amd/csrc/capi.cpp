@@ -223,17 +223,15 @@ int ot_rhs_nvar_out(ot_rhs_kind kind)
 
 int unzip(ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
 {
-    if (!tree || nvar <= 0 || nvar > 65535 || !zipped_dev || !padded_dev) return OT_E_BADARG;
-    if (tree->host.leaves.size() * static_cast<size_t>(nvar) > 0x7fffffffu) return OT_E_UNSUPPORTED;   // one workgroup each
-    if (int rc = ensure_device(tree)) return rc;
+    if (!tree || nvar <= 0 || !zipped_dev || !padded_dev) return OT_E_BADARG;
+    if (int rc = ensure_device(tree)) return rc;   // < 2^20 blocks, and the grid is at most 8 workgroups per block
     hipError_t e = launch_unzip(dev_view(tree), nvar, zipped_dev, padded_dev, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
 int unzip_centred(ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
 {
-    if (!tree || nvar <= 0 || nvar > 65535 || !zipped_dev || !padded_dev) return OT_E_BADARG;
-    if (tree->host.leaves.size() * static_cast<size_t>(nvar) > 0x7fffffffu) return OT_E_UNSUPPORTED;   // one workgroup each
+    if (!tree || nvar <= 0 || !zipped_dev || !padded_dev) return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
     hipError_t e = launch_unzip_centred(dev_view(tree), tree->host.level_start, false, nvar, zipped_dev, padded_dev,
                                         static_cast<hipStream_t>(hip_stream));
@@ -243,6 +241,7 @@ int unzip_centred(ot_tree* tree, int nvar, const double* zipped_dev, double* pad
 int zip(ot_tree* tree, int nvar, const double* padded_dev, double* zipped_dev, void* hip_stream)
 {
     if (!tree || nvar <= 0 || !zipped_dev || !padded_dev) return OT_E_BADARG;
+    if (tree->host.leaves.size() * static_cast<size_t>(nvar) > 0x7fffffffu) return OT_E_UNSUPPORTED;   // one workgroup each
     if (int rc = ensure_device(tree)) return rc;
     hipError_t e = launch_zip(dev_view(tree), nvar, padded_dev, zipped_dev, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);

@@ -204,6 +204,14 @@ def test_trees_of_a_million_blocks_are_refused_by_the_device_calls():
     assert e.value.status == octfd.OT_E_UNSUPPORTED
 
 
+def test_zip_refuses_more_workgroups_than_a_grid_holds():
+    # one workgroup per block and variable: 512 blocks x 2^23 variables would be 2^32 of them.
+    # The size check precedes every device call, so the fake pointers are never touched.
+    t = octfd.Tree.build(3, 3, np.zeros((0, 3), np.uint32), np.zeros(0, np.uint32))
+    fake = C.c_void_p(4096)
+    assert octfd.lib().zip(t._h, 1 << 23, fake, fake, None) == octfd.OT_E_UNSUPPORTED
+
+
 def test_bench_refuses_more_than_one_gpu_and_a_missing_gpu():
     import subprocess
     import sys

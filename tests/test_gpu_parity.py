@@ -162,3 +162,19 @@ def test_config4_sampled_parity(orc, dev):
     sample = np.unique(np.concatenate([np.arange(0, to.n, 41), np.flatnonzero(lev < lev.max())[::5]]))
     want = to.F(3, u, sigma=0.4, blocks=sample)
     assert_close(fd[:, torch.from_numpy(sample).to(dev)].cpu().numpy(), want, "C4 SYN24 sampled")
+
+
+@pytest.mark.parametrize("name", ["C3", "C3B"])
+def test_config3_rk_step_full_parity(orc, dev, name):
+    # the 47,783-block tree, wave system and Burgers equation: every value of one whole step
+    cfg = sd.CONFIGS[name]
+    kind = KIND[cfg["kind"]]
+    to, tg = trees(orc, name)
+    u = sd.make_fields(name, to.leaves).numpy()
+    dt = sd.time_step(cfg["lmax"])
+    want = to.rk4_step(kind, u, dt, sigma=sd.KO_SIGMA)
+    ud = torch.from_numpy(u).to(dev)
+    ws = torch.empty(tg.rk_workspace_bytes(kind) // 8, dtype=torch.float64, device=dev)
+    tg.rk_step(kind, ud, dt, ws, sigma=sd.KO_SIGMA)
+    assert_close(ud.cpu().numpy(), want, "rk_step " + name)
+    assert np.abs(want - u).max() > 0

@@ -117,6 +117,11 @@ def _ptr(t):
     return C.c_void_p(t.data_ptr())
 
 
+def _shape(t, want, name):
+    if tuple(t.shape) != tuple(want):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(want)))
+
+
 def _stream(stream):
     if stream is None:
         import torch
@@ -178,28 +183,31 @@ class Tree:
     # ---- device calls: tensors in, tensors out (outputs allocated by the caller) -------------
     def unzip(self, zipped, padded, stream=None):
         nvar = zipped.shape[0]
-        assert tuple(zipped.shape) == (nvar, self.n, 8, 8, 8) and tuple(padded.shape) == (nvar, self.n, 14, 14, 14)
+        _shape(zipped, (nvar, self.n, 8, 8, 8), "zipped")
+        _shape(padded, (nvar, self.n, 14, 14, 14), "padded")
         _check(lib().unzip(self._h, nvar, _ptr(zipped), _ptr(padded), _stream(stream)), "unzip")
 
     def unzip_centred(self, zipped, padded, stream=None):
         nvar = zipped.shape[0]
-        assert tuple(zipped.shape) == (nvar, self.n, 8, 8, 8) and tuple(padded.shape) == (nvar, self.n, 14, 14, 14)
+        _shape(zipped, (nvar, self.n, 8, 8, 8), "zipped")
+        _shape(padded, (nvar, self.n, 14, 14, 14), "padded")
         _check(lib().unzip_centred(self._h, nvar, _ptr(zipped), _ptr(padded), _stream(stream)), "unzip_centred")
 
     def zip(self, padded, zipped, stream=None):
         nvar = padded.shape[0]
-        assert tuple(zipped.shape) == (nvar, self.n, 8, 8, 8) and tuple(padded.shape) == (nvar, self.n, 14, 14, 14)
+        _shape(zipped, (nvar, self.n, 8, 8, 8), "zipped")
+        _shape(padded, (nvar, self.n, 14, 14, 14), "padded")
         _check(lib().zip(self._h, nvar, _ptr(padded), _ptr(zipped), _stream(stream)), "zip")
 
     def rhs_eval(self, kind, padded, rhs_padded, sigma=0.0, stream=None):
-        assert tuple(padded.shape) == (nvar_in(kind), self.n, 14, 14, 14)
-        assert tuple(rhs_padded.shape) == (nvar_out(kind), self.n, 14, 14, 14)
+        _shape(padded, (nvar_in(kind), self.n, 14, 14, 14), "padded")
+        _shape(rhs_padded, (nvar_out(kind), self.n, 14, 14, 14), "rhs_padded")
         p = RhsParams(float(sigma))
         _check(lib().rhs_eval(self._h, kind, C.byref(p), _ptr(padded), _ptr(rhs_padded), _stream(stream)), "rhs_eval")
 
     def rhs_eval_zipped(self, kind, zipped, rhs_zipped, sigma=0.0, stream=None):
-        assert tuple(zipped.shape) == (nvar_in(kind), self.n, 8, 8, 8)
-        assert tuple(rhs_zipped.shape) == (nvar_out(kind), self.n, 8, 8, 8)
+        _shape(zipped, (nvar_in(kind), self.n, 8, 8, 8), "zipped")
+        _shape(rhs_zipped, (nvar_out(kind), self.n, 8, 8, 8), "rhs_zipped")
         p = RhsParams(float(sigma))
         _check(lib().rhs_eval_zipped(self._h, kind, C.byref(p), _ptr(zipped), _ptr(rhs_zipped), _stream(stream)),
                "rhs_eval_zipped")
@@ -210,7 +218,7 @@ class Tree:
         return n.value
 
     def rk_step(self, kind, u, dt, workspace, sigma=0.0, stream=None):
-        assert tuple(u.shape) == (nvar_in(kind), self.n, 8, 8, 8)
+        _shape(u, (nvar_in(kind), self.n, 8, 8, 8), "u")
         p = RhsParams(float(sigma))
         nbytes = workspace.numel() * workspace.element_size()
         _check(lib().rk_step(self._h, kind, C.byref(p), float(dt), _ptr(u), _ptr(workspace), nbytes, _stream(stream)),
@@ -222,7 +230,7 @@ class Tree:
         return n.value
 
     def rk_step_centred(self, kind, u, dt, workspace, sigma=0.0, stream=None):
-        assert tuple(u.shape) == (nvar_in(kind), self.n, 8, 8, 8)
+        _shape(u, (nvar_in(kind), self.n, 8, 8, 8), "u")
         p = RhsParams(float(sigma))
         nbytes = workspace.numel() * workspace.element_size()
         _check(lib().rk_step_centred(self._h, kind, C.byref(p), float(dt), _ptr(u), _ptr(workspace), nbytes,
@@ -255,7 +263,7 @@ class Transfer:
 
     def apply(self, zipped_from, zipped_to, stream=None):
         nvar = zipped_from.shape[0]
-        assert tuple(zipped_from.shape) == (nvar, self.n_from, 8, 8, 8)
-        assert tuple(zipped_to.shape) == (nvar, self.n_to, 8, 8, 8)
+        _shape(zipped_from, (nvar, self.n_from, 8, 8, 8), "zipped_from")
+        _shape(zipped_to, (nvar, self.n_to, 8, 8, 8), "zipped_to")
         _check(lib().regrid_transfer(self._h, nvar, _ptr(zipped_from), _ptr(zipped_to), _stream(stream)),
                "regrid_transfer")

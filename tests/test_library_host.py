@@ -212,6 +212,19 @@ def test_zip_refuses_more_workgroups_than_a_grid_holds():
     assert octfd.lib().zip(t._h, 1 << 23, fake, fake, None) == octfd.OT_E_UNSUPPORTED
 
 
+def test_binding_rejects_wrong_shapes_and_host_tensors():
+    import torch
+    t = octfd.Tree.build(3, 3, np.zeros((0, 3), np.uint32), np.zeros(0, np.uint32))
+    z = torch.zeros((1, t.n, 8, 8, 8), dtype=torch.float64)
+    with pytest.raises(ValueError, match="padded has shape"):
+        t.unzip(z, torch.zeros((1, t.n, 14, 14, 13), dtype=torch.float64))
+    with pytest.raises(ValueError, match="u has shape"):
+        t.rk_step(octfd.WAVE, z, 1e-3, z)
+    # a host tensor of the right shape is not computed on: there is no CPU path
+    with pytest.raises(ValueError, match="CUDA tensor"):
+        t.unzip(z, torch.zeros((1, t.n, 14, 14, 14), dtype=torch.float64))
+
+
 def test_bench_refuses_more_than_one_gpu_and_a_missing_gpu():
     import subprocess
     import sys

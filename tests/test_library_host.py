@@ -204,6 +204,15 @@ def test_trees_of_a_million_blocks_are_refused_by_the_device_calls():
     assert e.value.status == octfd.OT_E_UNSUPPORTED
 
 
+def test_refinement_radius_is_a_strict_bound_in_the_library_too():
+    # hand-counted case of tests/test_oracle_tree.py: face neighbours at distance exactly R_3 stay whole
+    s = 1 << 17
+    c = 4 * s + s // 2
+    pt = np.array([(c, c, c)], np.uint32)
+    assert octfd.Tree.build(3, 4, pt, np.array([s // 2], np.uint32)).n == 519
+    assert octfd.Tree.build(3, 4, pt, np.array([s // 2 + 1], np.uint32)).n == 561
+
+
 def test_zip_refuses_more_workgroups_than_a_grid_holds():
     # one workgroup per block and variable: 512 blocks x 2^23 variables would be 2^32 of them.
     # The size check precedes every device call, so the fake pointers are never touched.

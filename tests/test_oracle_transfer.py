@@ -123,6 +123,19 @@ def test_injection_takes_the_coinciding_node(orc):
         orc.transfer(coarse, fine, f(xc, yc, zc)[None])      # four levels finer: refused
 
 
+def test_refinement_by_exactly_two_levels_is_refused_and_by_one_is_not(orc):
+    # the boundary of the rule: level 3 -> level 5 somewhere is refused, level 3 -> level 4 is served
+    coarse = uniform_tree(orc, 3)
+    u = np.zeros((1, coarse.n, 8, 8, 8))
+    with pytest.raises(ValueError):
+        orc.transfer(coarse, uniform_tree(orc, 5), u)
+    two = orc.Tree.build(3, 5, np.array([[300000, 500000, 700000]], np.uint32), np.array([30000, 30000], np.uint32))
+    assert two.leaves[:, 0].max() == 5 and two.leaves[:, 0].min() == 3
+    with pytest.raises(ValueError):
+        orc.transfer(coarse, two, u)
+    assert orc.transfer(coarse, uniform_tree(orc, 4), u).shape == (1, 4096, 8, 8, 8)
+
+
 def test_prolongation_converges_at_sixth_order(orc):
     errs = []
     for l in (3, 4):

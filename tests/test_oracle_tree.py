@@ -84,6 +84,7 @@ TINY = [
     (3, 5, [(524288, 524288, 524288)], [30000, 20000]),
     (3, 5, [(1000, 2000, 1040000)], [50000, 60000]),          # near a corner: periodic images matter
     (3, 5, [(200000, 800000, 400000), (230000, 790000, 420000)], [10, 70000]),  # only balance refines level 3
+    (3, 5, [(2000, 500000, 300000)], [10, 70000]),           # ... and it must do so across the periodic wrap in x
 ]
 
 
@@ -95,6 +96,18 @@ def test_build_equals_brute_force(orc, lmin, lmax, pts, radius):
     assert set(got) == want and len(got) == len(want)
     assert got == sorted(got, key=lambda r: morton(*r))      # storage order = Morton order
     assert len(set(r[0] for r in got)) > 1                   # the case really is adaptive
+
+
+def test_refinement_radius_is_a_strict_bound(orc):
+    # One seed point at the centre of level-3 octant (4,4,4), R_3 = half an octant edge: the six face
+    # neighbours lie at distance exactly R_3 and stay whole (the predicate is a strict <), so exactly one
+    # octant splits; one lattice unit more and they split too (the twelve edge neighbours, at
+    # sqrt(2) R_3, never do).  Counts by hand: 512 - 1 + 8 and 512 - 7 + 56.
+    s = 1 << 17
+    c = 4 * s + s // 2
+    pt = np.array([(c, c, c)], np.uint32)
+    assert orc.Tree.build(3, 4, pt, np.array([s // 2], np.uint32)).n == 519
+    assert orc.Tree.build(3, 4, pt, np.array([s // 2 + 1], np.uint32)).n == 561
 
 
 def check_structure(leaves):

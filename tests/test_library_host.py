@@ -234,6 +234,22 @@ def test_binding_rejects_wrong_shapes_and_host_tensors():
         t.unzip(z, torch.zeros((1, t.n, 14, 14, 14), dtype=torch.float64))
 
 
+def test_header_is_valid_c_and_a_c_program_can_use_the_library(tmp_path):
+    # the boundary is a C ABI: compile a C11 client against include/octfd.h with gcc (not hipcc, not C++),
+    # link it to the built library and run the host-only calls
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "host_calls")
+    libdir = os.path.dirname(octfd.LIB_PATH)
+    cc = subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(root, "include"),
+                         os.path.join(root, "tests", "c_abi", "host_calls.c"), "-o", exe, "-L", libdir, "-loctfd",
+                         "-Wl,-rpath," + libdir], capture_output=True, text=True, timeout=120)
+    assert cc.returncode == 0, cc.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    assert r.stdout.strip() == "blocks 519 fine 8 copies 519 self 0"
+
+
 def test_bench_refuses_more_than_one_gpu_and_a_missing_gpu():
     import subprocess
     import sys

@@ -150,8 +150,11 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
     } else if (KIND == OT_RHS_WAVE) {
         const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
         stage(0);
+        prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(1), tid);   // pi is on its way while u is differentiated
         const PointOps pu = point_ops<true>(tiles, c, sigma, ih, ih2);
-        stage(1);
+        __syncthreads();
+        commit<ZIN, NPLAN, PLAN_FACE, CENTRED>(tiles, scratch, bi, fp, pv, cv, false, var_base(1), tid, pad_base(1));
+        __syncthreads();
         const PointOps pp = point_ops<false>(tiles, c, sigma, ih, ih2);
         emit<EPI>(a, nb, 0, b, o8, p8, pp.u0 + pu.ko, e0);
         emit<EPI>(a, nb, 1, b, o8, p8, pu.lap + pp.ko, e1);

@@ -260,12 +260,12 @@ __device__ __forceinline__ void interp_faces_centred(double* tile, double* scrat
 //               coarser leaves.  `base` is that variable's zipped array (ZIN) or this block's padded
 //               data.  All threads call both.  commit() does NOT end with a barrier.
 // USE = how many plan entries per thread are in use (PLAN_FACE: faces only).
-template <int NPLAN, int USE>
-__device__ __forceinline__ void prefetch(double (&v)[NPLAN], const FillPlan<NPLAN>& fp, const double* __restrict__ base, int tid)
+template <int NPLAN, int USE, bool REG>
+__device__ __forceinline__ void prefetch(double (&v)[NPLAN], const FillPlan<NPLAN, REG>& fp, const double* __restrict__ base, int tid)
 {
     uint32_t off[USE];
 #pragma unroll
-    for (int m = 0; m < USE; ++m) off[m] = fp.src[m * NTHREADS + tid];
+    for (int m = 0; m < USE; ++m) off[m] = fp.get_src(m, tid);
     // the last entry in use may reach beyond the face prefix: read element 0 instead
     if (USE == PLAN_FACE && NPLAN > PLAN_FACE && tid + (USE - 1) * NTHREADS >= NFACE) off[USE - 1] = 0;
 #pragma unroll
@@ -286,8 +286,8 @@ __device__ __forceinline__ void coarse_prefetch(double (&cv)[CPRE], const BlockI
 
 // CENTRED: ghost values from coarser leaves follow the centred rule and come from pbase (that
 // variable's padded source leaves).
-template <bool ZIN, int NPLAN, int USE, bool CENTRED = false>
-__device__ __forceinline__ void commit(double* tile, double* scratch, const BlockInfo& bi, const FillPlan<NPLAN>& fp,
+template <bool ZIN, int NPLAN, int USE, bool CENTRED = false, bool REG>
+__device__ __forceinline__ void commit(double* tile, double* scratch, const BlockInfo& bi, const FillPlan<NPLAN, REG>& fp,
                                        const double (&v)[NPLAN], const double (&cv)[CPRE], bool have_cv,
                                        const double* __restrict__ base, int tid, const double* __restrict__ pbase = nullptr)
 {

@@ -82,7 +82,7 @@ constexpr int NSTREAM = 25;
 __device__ __forceinline__ int syn24_stream(int t) { return t == 0 ? 10 : (t <= 10 ? 10 - t : 34 - t); }
 
 template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
-__global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr, RhsArgs a)
+__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTree tr, RhsArgs a)
 {
     static_assert(ZIN || !CENTRED, "the centred ghost rule applies to zipped input");
     constexpr int NBUF = KIND == OT_RHS_SYN24 ? 2 : 1;
@@ -96,7 +96,8 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
     // second derivatives (SYN24 only) read the edge slabs of the tile too
     constexpr int NPLAN = KIND == OT_RHS_SYN24 ? PLAN_EDGE : PLAN_FACE;
     constexpr int NPOINTS = KIND == OT_RHS_SYN24 ? NEDGE : NFACE;
-    __shared__ uint32_t plan_src[NPLAN * NTHREADS];
+    constexpr bool PLAN_IN_REGS = KIND != OT_RHS_SYN24;
+    __shared__ uint32_t plan_src[PLAN_IN_REGS ? 1 : NPLAN * NTHREADS];
 
     const int tid = threadIdx.x;
     const int64_t nb = tr.nb;
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(NTHREADS, WAVES_PER_SIMD) void k_rhs(DeviceTree tr,
     const double ih = (double)(NPT << bi.level), ih2 = ih * ih;
     const double sigma = a.sigma;
 
-    FillPlan<NPLAN> fp;
+    FillPlan<NPLAN, PLAN_IN_REGS> fp;
     fp.src = plan_src;
     if (ZIN) make_plan_zipped<NPLAN, NPOINTS>(fp, bi, tid);
     else make_plan_padded<NPLAN, NPOINTS>(fp, tid);

@@ -16,7 +16,9 @@ constexpr int K_COARSER = 2, K_SAME = 0;
 // stride of 200 = 8 (mod 32).  A wavefront holds one j row of the block, its lanes run over
 // (i, k): the eight x-contiguous values of four consecutive k planes then fall into 32 different
 // 8-byte banks, and shifting the access by any stencil offset keeps that property.
-constexpr int WAVES_PER_SIMD = 4;        // 128 VGPRs per lane: two workgroups of the stage kernels share a compute unit
+// wavefronts per SIMD the right-hand-side kernels are compiled for: the 24-field kernel 4 (128 VGPRs per lane, two
+// workgroups share a compute unit, which is also what its LDS allows); the other kinds 8 (64 VGPRs, four workgroups)
+constexpr int waves_per_simd(int kind) { return kind == OT_RHS_SYN24 ? 4 : 8; }
 constexpr int RS = NP;                   // 14
 constexpr int PS = NP * RS + 4;          // 200
 constexpr int TILE = NP * PS;            // 14 planes
@@ -156,12 +158,17 @@ __device__ __forceinline__ void tile_point(int p, int& ii, int& jj, int& kk)
 // Entries with nothing to copy (beyond the range in use, or interpolated later) read element 0 and
 // write to DUMMY, a padding slot of the tile that no stencil reads; the copy loop is branch-free.
 constexpr int DUMMY = NP * RS;   // first padding slot behind plane 0
-// src: byte offset in the source array, kept in LDS as src[m * NTHREADS + tid] (it is needed once
-// per variable and registers are scarce); dst: tile index, two 16-bit values per register
-template <int NPLAN>
+// src: byte offset in the source array.  It is needed once per variable: the 24-field kernel, short of
+// registers, keeps it in LDS as src[m * NTHREADS + tid]; with REG the entries are registers (the other
+// kinds: 8 KB less LDS, which lets a fourth workgroup onto the compute unit).
+// dst: tile index, two 16-bit values per register.
+template <int NPLAN, bool REG = false>
 struct FillPlan {
     uint32_t* src;
+    uint32_t srcr[REG ? NPLAN : 1];
     uint32_t dstp[(NPLAN + 1) / 2];
+    __device__ __forceinline__ uint32_t get_src(int m, int tid) const { return REG ? srcr[m] : src[m * NTHREADS + tid]; }
+    __device__ __forceinline__ void set_src(int m, int tid, uint32_t v) { if (REG) srcr[m] = v; else src[m * NTHREADS + tid] = v; }
     __device__ __forceinline__ int dst(int m) const { return (dstp[m >> 1] >> (16 * (m & 1))) & 0xffff; }
     __device__ __forceinline__ void set_dst(int m, int v) { dstp[m >> 1] = (m & 1) ? (dstp[m >> 1] | ((uint32_t)v << 16)) : (uint32_t)v; }
 };
@@ -171,8 +178,8 @@ static_assert(SCRATCH >= 1024 + 2 * 512, "face interpolation staging: 8 x 128 pe
 // Source of every padded point this thread fills, as a byte offset into one variable's zipped
 // array (same-level copy or injection from a finer leaf).  Points whose source is coarser are left
 // to the interpolation passes.  NPOINTS = how long a prefix of the enumeration is planned.
-template <int NPLAN, int NPOINTS>
-__device__ __forceinline__ void make_plan_zipped(FillPlan<NPLAN>& fp, const BlockInfo& bi, int tid)
+template <int NPLAN, int NPOINTS, bool REG>
+__device__ __forceinline__ void make_plan_zipped(FillPlan<NPLAN, REG>& fp, const BlockInfo& bi, int tid)
 {
 #pragma unroll
     for (int m = 0; m < NPLAN; ++m) {
@@ -208,14 +215,14 @@ __device__ __forceinline__ void make_plan_zipped(FillPlan<NPLAN>& fp, const Bloc
                 src = elem * 8u;
             }
         }
-        fp.src[m * NTHREADS + tid] = src;
+        fp.set_src(m, tid, src);
         fp.set_dst(m, dst);
     }
 }
 
 // same for a padded source block (plain copy)
-template <int NPLAN, int NPOINTS>
-__device__ __forceinline__ void make_plan_padded(FillPlan<NPLAN>& fp, int tid)
+template <int NPLAN, int NPOINTS, bool REG>
+__device__ __forceinline__ void make_plan_padded(FillPlan<NPLAN, REG>& fp, int tid)
 {
 #pragma unroll
     for (int m = 0; m < NPLAN; ++m) {
@@ -223,7 +230,7 @@ __device__ __forceinline__ void make_plan_padded(FillPlan<NPLAN>& fp, int tid)
         const bool ok = p < NPOINTS;
         int ii, jj, kk;
         tile_point(ok ? p : 0, ii, jj, kk);
-        fp.src[m * NTHREADS + tid] = ok ? (uint32_t)((kk * NP + jj) * NP + ii) * 8u : 0u;
+        fp.set_src(m, tid, ok ? (uint32_t)((kk * NP + jj) * NP + ii) * 8u : 0u);
         fp.set_dst(m, ok ? tidx(kk, jj, ii) : DUMMY);
     }
 }

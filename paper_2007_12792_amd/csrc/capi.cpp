@@ -20,6 +20,7 @@ struct ot_tree {
     int32_t* d_by_level = nullptr;
     int32_t* d_src_slot = nullptr;
     int32_t* d_src_by_level = nullptr;
+    int32_t* d_by_kind = nullptr;
     int device = -1;   // device the tables live on, -1 = not uploaded
 };
 
@@ -65,15 +66,17 @@ int ensure_device(ot_tree* t)
     const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
     // one allocation for all tables, each part 256-byte aligned
     const HostTree& h = t->host;
-    const void* part[6] = {h.leaves.data(), h.ghost.data(), h.coarse.data(), h.by_level.data(), h.src_slot.data(),
-                           h.src_by_level.data()};
-    const size_t bytes[6] = {nl, ng, h.coarse.size() * sizeof(int32_t), h.by_level.size() * sizeof(int32_t),
-                             h.src_slot.size() * sizeof(int32_t), h.src_by_level.size() * sizeof(int32_t)};
-    size_t off[7] = {0};
-    for (int i = 0; i < 6; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
+    constexpr int kParts = 7;
+    const void* part[kParts] = {h.leaves.data(), h.ghost.data(), h.coarse.data(), h.by_level.data(), h.src_slot.data(),
+                                h.src_by_level.data(), h.by_kind.data()};
+    const size_t bytes[kParts] = {nl, ng, h.coarse.size() * sizeof(int32_t), h.by_level.size() * sizeof(int32_t),
+                                  h.src_slot.size() * sizeof(int32_t), h.src_by_level.size() * sizeof(int32_t),
+                                  h.by_kind.size() * sizeof(int32_t)};
+    size_t off[kParts + 1] = {0};
+    for (int i = 0; i < kParts; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
     char* base = nullptr;
-    if ((e = hipMalloc(reinterpret_cast<void**>(&base), off[6])) != hipSuccess) return hip_fail(e);
-    for (int i = 0; i < 6 && e == hipSuccess; ++i)
+    if ((e = hipMalloc(reinterpret_cast<void**>(&base), off[kParts])) != hipSuccess) return hip_fail(e);
+    for (int i = 0; i < kParts && e == hipSuccess; ++i)
         if (bytes[i]) e = hipMemcpy(base + off[i], part[i], bytes[i], hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         (void)hipFree(base);
@@ -85,6 +88,7 @@ int ensure_device(ot_tree* t)
     t->d_by_level = reinterpret_cast<int32_t*>(base + off[3]);
     t->d_src_slot = reinterpret_cast<int32_t*>(base + off[4]);
     t->d_src_by_level = reinterpret_cast<int32_t*>(base + off[5]);
+    t->d_by_kind = reinterpret_cast<int32_t*>(base + off[6]);
     t->device = dev;
     return OT_OK;
 }
@@ -124,7 +128,8 @@ int ensure_device(ot_transfer* p)
 DeviceTree dev_view(const ot_tree* t)
 {
     return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, t->d_by_level, static_cast<int64_t>(t->host.leaves.size()),
-                      t->d_src_slot, t->d_src_by_level, static_cast<int64_t>(t->host.src_by_level.size())};
+                      t->d_src_slot, t->d_src_by_level, static_cast<int64_t>(t->host.src_by_level.size()),
+                      t->d_by_kind, t->host.n_plain};
 }
 
 bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }

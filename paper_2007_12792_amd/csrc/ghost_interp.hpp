@@ -286,7 +286,8 @@ __device__ __forceinline__ void coarse_prefetch(double (&cv)[CPRE], const BlockI
 
 // CENTRED: ghost values from coarser leaves follow the centred rule and come from pbase (that
 // variable's padded source leaves).
-template <bool ZIN, int NPLAN, int USE, bool CENTRED = false, bool REG>
+// INTERP = false: the caller knows that the block has no coarser source (the interpolation is compiled out).
+template <bool ZIN, int NPLAN, int USE, bool CENTRED = false, bool INTERP = true, bool REG>
 __device__ __forceinline__ void commit(double* tile, double* scratch, const BlockInfo& bi, const FillPlan<NPLAN, REG>& fp,
                                        const double (&v)[NPLAN], const double (&cv)[CPRE], bool have_cv,
                                        const double* __restrict__ base, int tid, const double* __restrict__ pbase = nullptr)
@@ -297,7 +298,7 @@ __device__ __forceinline__ void commit(double* tile, double* scratch, const Bloc
         if (USE == PLAN_FACE && NPLAN > PLAN_FACE && m == USE - 1 && tid + m * NTHREADS >= NFACE) d = DUMMY;
         tile[d] = v[m];
     }
-    if (!ZIN || bi.cs[0] < 0) return;
+    if (!ZIN || !INTERP || bi.cs[0] < 0) return;
     // Control flow below is uniform over the workgroup.
     if (CENTRED) {
         if (USE == PLAN_FACE) interp_faces_centred(tile, scratch, bi, pbase, tid);

@@ -81,9 +81,13 @@ __device__ __forceinline__ double syn24_combine(const Syn24Part& p, int f, doubl
 constexpr int NSTREAM = 25;
 __device__ __forceinline__ int syn24_stream(int t) { return t == 0 ? 10 : (t <= 10 ? 10 - t : 34 - t); }
 
-template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
-__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTree tr, RhsArgs a)
+// The kernel works on the blocks list[0 .. count) (list == nullptr: blocks 0 .. count-1).  COARSE = false
+// promises that none of them has a coarser source: no box plan, no interpolation code.
+template <int KIND, bool ZIN, int EPI, bool CENTRED = false, bool COARSE = true>
+__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTree tr, RhsArgs a, const int32_t* __restrict__ list,
+                                                                        int64_t count)
 {
+    static_assert(COARSE || !CENTRED, "the ghost rules differ only where a coarser source exists");
     static_assert(ZIN || !CENTRED, "the centred ghost rule applies to zipped input");
     constexpr int NBUF = KIND == OT_RHS_SYN24 ? 2 : 1;
     __shared__ double tiles[NBUF * TILE];
@@ -101,11 +105,12 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
 
     const int tid = threadIdx.x;
     const int64_t nb = tr.nb;
-    const int64_t b = block_of_workgroup(blockIdx.x);
-    if (b >= nb) return;                             // uniform over the workgroup
+    const int64_t q = block_of_workgroup(blockIdx.x);
+    if (q >= count) return;                          // uniform over the workgroup
+    const int64_t b = list ? list[q] : q;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
-    if (tid == 0 && (KIND == OT_RHS_SYN24 || CENTRED)) make_box_plan(bi);   // read only after the next barrier
+    if (tid == 0 && COARSE && (KIND == OT_RHS_SYN24 || CENTRED)) make_box_plan(bi);   // read only after the next barrier
 
     int i, j, k;
     point_of(tid, i, j, k);
@@ -132,7 +137,7 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
     auto stage = [&](int v) {   // bring variable v into tile buffer 0 (barrier before and after)
         __syncthreads();
         prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(v), tid);
-        commit<ZIN, NPLAN, PLAN_FACE, CENTRED>(tiles, scratch, bi, fp, pv, cv, false, var_base(v), tid, pad_base(v));
+        commit<ZIN, NPLAN, PLAN_FACE, CENTRED, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(v), tid, pad_base(v));
         __syncthreads();
     };
     auto centre = [&](int v) -> double {   // this thread's own value of variable v
@@ -154,7 +159,7 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
         prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(1), tid);   // pi is on its way while u is differentiated
         const PointOps pu = point_ops<true>(tiles, c, sigma, ih, ih2);
         __syncthreads();
-        commit<ZIN, NPLAN, PLAN_FACE, CENTRED>(tiles, scratch, bi, fp, pv, cv, false, var_base(1), tid, pad_base(1));
+        commit<ZIN, NPLAN, PLAN_FACE, CENTRED, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(1), tid, pad_base(1));
         __syncthreads();
         const PointOps pp = point_ops<false>(tiles, c, sigma, ih, ih2);
         emit<EPI>(a, nb, 0, b, o8, p8, pp.u0 + pu.ko, e0);
@@ -197,7 +202,7 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
             if (t + 1 < NSTREAM) {
                 f1 = syn24_stream(t + 1);
                 prefetch<NPLAN, NEXT_USE>(pv, fp, var_base(f1), tid);
-                if (ZIN && !CENTRED && NEXT_USE == PLAN_FACE) coarse_prefetch(cv, bi, var_base(f1), tid);
+                if (ZIN && COARSE && !CENTRED && NEXT_USE == PLAN_FACE) coarse_prefetch(cv, bi, var_base(f1), tid);
             }
             l.unext = centre((f + 11) % 24);
             l.eo = epi_prefetch<EPI>(a, nb, f, o8);
@@ -221,7 +226,7 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
             const double lap = fma(2.0, off, p.diag);
             stg(stash_base(10 + f), s8, lap);
             emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l.unext), l.eo);
-            commit<ZIN, NPLAN, NEXT_USE, CENTRED>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, NEXT_USE == PLAN_FACE, var_base(f1), tid, pad_base(f1));
+            commit<ZIN, NPLAN, NEXT_USE, CENTRED, COARSE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, NEXT_USE == PLAN_FACE, var_base(f1), tid, pad_base(f1));
             __syncthreads();
         };
         // pass over a variable without second derivatives (23..10)
@@ -234,7 +239,7 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
             const Syn24Part p = syn24_axes<false>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
             emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, l.lap, halpha, l.unext), l.eo);
             if (t + 1 < NSTREAM) {
-                commit<ZIN, NPLAN, PLAN_FACE, CENTRED>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, true, var_base(f1), tid, pad_base(f1));
+                commit<ZIN, NPLAN, PLAN_FACE, CENTRED, COARSE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, true, var_base(f1), tid, pad_base(f1));
                 __syncthreads();
             }
         };
@@ -243,11 +248,11 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
             const int f = syn24_stream(0), f1 = syn24_stream(1);
             prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(f), tid);
             if (CENTRED) __syncthreads();            // the box plan, made by one thread, is read in this commit already
-            commit<ZIN, NPLAN, PLAN_FACE, CENTRED>(tiles, scratch, bi, fp, pv, cv, false, var_base(f), tid, pad_base(f));
+            commit<ZIN, NPLAN, PLAN_FACE, CENTRED, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(f), tid, pad_base(f));
             __syncthreads();
             prefetch<NPLAN, PLAN_EDGE>(pv, fp, var_base(f1), tid);
             nx = d1_at(tiles, c, 1, ih); ny = d1_at(tiles, c, RS, ih); nz = d1_at(tiles, c, PS, ih);
-            commit<ZIN, NPLAN, PLAN_EDGE, CENTRED>(tiles + TILE, scratch, bi, fp, pv, cv, false, var_base(f1), tid, pad_base(f1));
+            commit<ZIN, NPLAN, PLAN_EDGE, CENTRED, COARSE>(tiles + TILE, scratch, bi, fp, pv, cv, false, var_base(f1), tid, pad_base(f1));
             __syncthreads();
         }
 #pragma unroll 1
@@ -378,7 +383,20 @@ __global__ __launch_bounds__(NTHREADS) void k_zip(int64_t nblocks, const double*
 template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
 hipError_t launch_one(const DeviceTree& t, const RhsArgs& a, hipStream_t s)
 {
-    hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, CENTRED>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
+    if constexpr (KIND == OT_RHS_SYN24 && ZIN) {
+        // two launches: the blocks without a coarser source run a kernel compiled without the interpolation
+        // (fewer live registers; on a uniform tree 5 % faster), the others the full kernel
+        const int64_t n_coarse = t.nb - t.n_plain;
+        if (t.n_plain > 0)
+            hipLaunchKernelGGL((k_rhs<KIND, true, EPI, false, false>), dim3(grid_for_blocks(t.n_plain)), dim3(NTHREADS), 0, s, t, a,
+                               t.by_kind, t.n_plain);
+        if (n_coarse > 0)
+            hipLaunchKernelGGL((k_rhs<KIND, true, EPI, CENTRED, true>), dim3(grid_for_blocks(n_coarse)), dim3(NTHREADS), 0, s, t, a,
+                               t.by_kind + t.n_plain, n_coarse);
+    } else {
+        hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, CENTRED, true>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a,
+                           static_cast<const int32_t*>(nullptr), t.nb);
+    }
     return hipGetLastError();
 }
 

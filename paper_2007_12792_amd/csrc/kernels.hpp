@@ -18,6 +18,8 @@ struct DeviceTree {
     const int32_t* src_slot;     // [nb] position of a source leaf in a compact padded array, -1 for the others
     const int32_t* src_by_level; // [n_src] ids of the source leaves sorted by level
     int64_t n_src;
+    const int32_t* by_kind;      // [nb] first the n_plain blocks without a coarser source, then the others
+    int64_t n_plain;
 };
 
 // how the right-hand side leaves the kernel

@@ -238,6 +238,15 @@ void make_level_lists(HostTree& t)
     t.src_by_level.assign(n_src, 0);
     for (size_t b = 0; b < nb; ++b)
         if (t.src_slot[b] >= 0) t.src_by_level[scount[t.leaves[b].level]++] = static_cast<int32_t>(b);
+
+    // blocks without / with a coarser source
+    t.by_kind.clear();
+    t.by_kind.reserve(nb);
+    for (size_t b = 0; b < nb; ++b)
+        if (t.coarse[b * kCoarseRow] < 0) t.by_kind.push_back(static_cast<int32_t>(b));
+    t.n_plain = static_cast<int64_t>(t.by_kind.size());
+    for (size_t b = 0; b < nb; ++b)
+        if (t.coarse[b * kCoarseRow] >= 0) t.by_kind.push_back(static_cast<int32_t>(b));
 }
 
 int build_tree(const ot_build_params& p, HostTree& out)

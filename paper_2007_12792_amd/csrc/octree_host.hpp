@@ -33,6 +33,11 @@ struct HostTree {
     // src_by_level / src_level_start list them by level like by_level / level_start.
     std::vector<int32_t> src_slot, src_by_level;
     int64_t src_level_start[21] = {};
+    // Block ids split by whether a block takes ghost values from a coarser leaf: first the n_plain blocks
+    // that do not (Morton order), then the others (Morton order).  The 24-field kernel is launched once per
+    // part, so that the part without interpolation is compiled without it.
+    std::vector<int32_t> by_kind;
+    int64_t n_plain = 0;
 };
 
 // Each returns an OT_* status.

@@ -236,7 +236,7 @@ def main():
                    "wall_s_timed_region": wall},
         "roofline": {"bound": "hbm", "kernel": "k_rhs<%s, zipped in, %s> (%d per step%s)"
                                % (cfg["kind"], "plain output" if single_rhs else "RK-stage epilogue", launches_per_step,
-                                  "; each is two launches, blocks without / with a coarser neighbour" if cfg["kind"] == "SYN24" else ""),
+                                  ""),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "launch_ms": launch_ms, "algorithmic_bytes_per_launch": bytes_per_launch,
                      "traffic": None if single_rhs else measured_traffic(args.config, nb),

@@ -20,7 +20,7 @@ struct ot_tree {
     int32_t* d_by_level = nullptr;
     int32_t* d_src_slot = nullptr;
     int32_t* d_src_by_level = nullptr;
-    int32_t* d_by_kind = nullptr;
+    int32_t* d_sched = nullptr;
     int device = -1;   // device the tables live on, -1 = not uploaded
 };
 
@@ -68,10 +68,10 @@ int ensure_device(ot_tree* t)
     const HostTree& h = t->host;
     constexpr int kParts = 7;
     const void* part[kParts] = {h.leaves.data(), h.ghost.data(), h.coarse.data(), h.by_level.data(), h.src_slot.data(),
-                                h.src_by_level.data(), h.by_kind.data()};
+                                h.src_by_level.data(), h.sched.data()};
     const size_t bytes[kParts] = {nl, ng, h.coarse.size() * sizeof(int32_t), h.by_level.size() * sizeof(int32_t),
                                   h.src_slot.size() * sizeof(int32_t), h.src_by_level.size() * sizeof(int32_t),
-                                  h.by_kind.size() * sizeof(int32_t)};
+                                  h.sched.size() * sizeof(int32_t)};
     size_t off[kParts + 1] = {0};
     for (int i = 0; i < kParts; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
     char* base = nullptr;
@@ -88,7 +88,7 @@ int ensure_device(ot_tree* t)
     t->d_by_level = reinterpret_cast<int32_t*>(base + off[3]);
     t->d_src_slot = reinterpret_cast<int32_t*>(base + off[4]);
     t->d_src_by_level = reinterpret_cast<int32_t*>(base + off[5]);
-    t->d_by_kind = reinterpret_cast<int32_t*>(base + off[6]);
+    t->d_sched = reinterpret_cast<int32_t*>(base + off[6]);
     t->device = dev;
     return OT_OK;
 }
@@ -129,7 +129,7 @@ DeviceTree dev_view(const ot_tree* t)
 {
     return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, t->d_by_level, static_cast<int64_t>(t->host.leaves.size()),
                       t->d_src_slot, t->d_src_by_level, static_cast<int64_t>(t->host.src_by_level.size()),
-                      t->d_by_kind, t->host.n_plain};
+                      t->d_sched, static_cast<int64_t>(t->host.sched.size())};
 }
 
 bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }

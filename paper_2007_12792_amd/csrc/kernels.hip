@@ -81,33 +81,37 @@ __device__ __forceinline__ double syn24_combine(const Syn24Part& p, int f, doubl
 constexpr int NSTREAM = 25;
 __device__ __forceinline__ int syn24_stream(int t) { return t == 0 ? 10 : (t <= 10 ? 10 - t : 34 - t); }
 
-// The kernel works on the blocks list[0 .. count) (list == nullptr: blocks 0 .. count-1).  COARSE = false
-// promises that none of them has a coarser source: no box plan, no interpolation code.
-template <int KIND, bool ZIN, int EPI, bool CENTRED = false, bool COARSE = true>
-__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTree tr, RhsArgs a, const int32_t* __restrict__ list,
-                                                                        int64_t count)
+// LDS of the right-hand-side kernels (in doubles / words)
+template <int KIND, bool ZIN>
+struct RhsLds {
+    static constexpr int NBUF = KIND == OT_RHS_SYN24 ? 2 : 1;
+    // SYN24 keeps wy / wz in `scratch` and stages whole boxes of coarser leaves there; the other kinds read face
+    // slabs only, whose interpolation needs 2,048 doubles
+    static constexpr int FACE_STAGING = 1024 + 2 * 512;
+    static_assert(FACE_STAGING >= 810, "centred interpolation of one 3 x 8 x 8 face slab");
+    static constexpr int NSCRATCH = KIND == OT_RHS_SYN24 ? SCRATCH : (ZIN ? FACE_STAGING : 1);
+    // second derivatives (SYN24 only) read the edge slabs of the tile too
+    static constexpr int NPLAN = KIND == OT_RHS_SYN24 ? PLAN_EDGE : PLAN_FACE;
+    static constexpr int NPOINTS = KIND == OT_RHS_SYN24 ? NEDGE : NFACE;
+    static constexpr bool PLAN_IN_REGS = KIND != OT_RHS_SYN24;
+    static constexpr int NPLAN_SRC = PLAN_IN_REGS ? 1 : NPLAN * NTHREADS;
+};
+
+// One block, all its variables: the whole right-hand side (and Runge-Kutta stage update) of block b.
+// COARSE = false promises that b has no coarser source: no box plan, no interpolation code (for the
+// 24-field kernel that is 2 spilled registers instead of 11, and 5 % less time on a uniform tree).
+// The LDS arrays belong to the calling kernel (sizes: RhsLds).
+template <int KIND, bool ZIN, int EPI, bool CENTRED, bool COARSE>
+__device__ __forceinline__ void rhs_block(const DeviceTree& tr, const RhsArgs& a, const int64_t b, double* tiles, double* scratch,
+                                          BlockInfo& bi, uint32_t* plan_src)
 {
     static_assert(COARSE || !CENTRED, "the ghost rules differ only where a coarser source exists");
     static_assert(ZIN || !CENTRED, "the centred ghost rule applies to zipped input");
-    constexpr int NBUF = KIND == OT_RHS_SYN24 ? 2 : 1;
-    __shared__ double tiles[NBUF * TILE];
-    // SYN24 keeps wy / wz here and stages whole boxes of coarser leaves; the other kinds read face slabs
-    // only, whose interpolation needs 2,048 doubles (and lets three workgroups share a compute unit)
-    constexpr int FACE_STAGING = 1024 + 2 * 512;
-    static_assert(FACE_STAGING >= 810, "centred interpolation of one 3 x 8 x 8 face slab");
-    __shared__ double scratch[KIND == OT_RHS_SYN24 ? SCRATCH : (ZIN ? FACE_STAGING : 1)];
-    __shared__ BlockInfo bi;
-    // second derivatives (SYN24 only) read the edge slabs of the tile too
-    constexpr int NPLAN = KIND == OT_RHS_SYN24 ? PLAN_EDGE : PLAN_FACE;
-    constexpr int NPOINTS = KIND == OT_RHS_SYN24 ? NEDGE : NFACE;
-    constexpr bool PLAN_IN_REGS = KIND != OT_RHS_SYN24;
-    __shared__ uint32_t plan_src[PLAN_IN_REGS ? 1 : NPLAN * NTHREADS];
+    constexpr int NPLAN = RhsLds<KIND, ZIN>::NPLAN, NPOINTS = RhsLds<KIND, ZIN>::NPOINTS;
+    constexpr bool PLAN_IN_REGS = RhsLds<KIND, ZIN>::PLAN_IN_REGS;
 
     const int tid = threadIdx.x;
     const int64_t nb = tr.nb;
-    const int64_t q = block_of_workgroup(blockIdx.x);
-    if (q >= count) return;                          // uniform over the workgroup
-    const int64_t b = list ? list[q] : q;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
     if (tid == 0 && COARSE && (KIND == OT_RHS_SYN24 || CENTRED)) make_box_plan(bi);   // read only after the next barrier
@@ -263,6 +267,37 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
     }
 }
 
+template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
+__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTree tr, RhsArgs a)
+{
+    using L = RhsLds<KIND, ZIN>;
+    __shared__ double tiles[L::NBUF * TILE];
+    __shared__ double scratch[L::NSCRATCH];
+    __shared__ BlockInfo bi;
+    __shared__ uint32_t plan_src[L::NPLAN_SRC];
+    const int64_t b = block_of_workgroup(blockIdx.x);
+    if (b >= tr.nb) return;                          // uniform over the workgroup
+    rhs_block<KIND, ZIN, EPI, CENTRED, true>(tr, a, b, tiles, scratch, bi, plan_src);
+}
+
+// The same over the tree's schedule (see HostTree::sched): chunks of blocks without a coarser source, which take
+// the path compiled without interpolation, dealt in among chunks of blocks with one.
+template <int KIND, int EPI, bool CENTRED = false>
+__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs_sched(DeviceTree tr, RhsArgs a)
+{
+    using L = RhsLds<KIND, true>;
+    __shared__ double tiles[L::NBUF * TILE];
+    __shared__ double scratch[L::NSCRATCH];
+    __shared__ BlockInfo bi;
+    __shared__ uint32_t plan_src[L::NPLAN_SRC];
+    const int64_t q = block_of_workgroup(blockIdx.x);
+    if (q >= tr.n_sched) return;                     // uniform over the workgroup, like everything below
+    const int32_t e = tr.sched[q];
+    if (e < 0) return;                               // padding of a chunk
+    if (e & kSchedCoarse) rhs_block<KIND, true, EPI, CENTRED, true>(tr, a, e & ~kSchedCoarse, tiles, scratch, bi, plan_src);
+    else rhs_block<KIND, true, EPI, false, false>(tr, a, e, tiles, scratch, bi, plan_src);
+}
+
 // ---------------------------------------------------------------- unzip / zip kernels
 
 __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, const double* __restrict__ zipped, double* __restrict__ padded)
@@ -383,20 +418,10 @@ __global__ __launch_bounds__(NTHREADS) void k_zip(int64_t nblocks, const double*
 template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
 hipError_t launch_one(const DeviceTree& t, const RhsArgs& a, hipStream_t s)
 {
-    if constexpr (KIND == OT_RHS_SYN24 && ZIN) {
-        // two launches: the blocks without a coarser source run a kernel compiled without the interpolation
-        // (fewer live registers; on a uniform tree 5 % faster), the others the full kernel
-        const int64_t n_coarse = t.nb - t.n_plain;
-        if (t.n_plain > 0)
-            hipLaunchKernelGGL((k_rhs<KIND, true, EPI, false, false>), dim3(grid_for_blocks(t.n_plain)), dim3(NTHREADS), 0, s, t, a,
-                               t.by_kind, t.n_plain);
-        if (n_coarse > 0)
-            hipLaunchKernelGGL((k_rhs<KIND, true, EPI, CENTRED, true>), dim3(grid_for_blocks(n_coarse)), dim3(NTHREADS), 0, s, t, a,
-                               t.by_kind + t.n_plain, n_coarse);
-    } else {
-        hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, CENTRED, true>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a,
-                           static_cast<const int32_t*>(nullptr), t.nb);
-    }
+    if constexpr (KIND == OT_RHS_SYN24 && ZIN)
+        hipLaunchKernelGGL((k_rhs_sched<KIND, EPI, CENTRED>), dim3(grid_for_blocks(t.n_sched)), dim3(NTHREADS), 0, s, t, a);
+    else
+        hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, CENTRED>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
     return hipGetLastError();
 }
 

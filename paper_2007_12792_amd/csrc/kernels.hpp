@@ -18,9 +18,13 @@ struct DeviceTree {
     const int32_t* src_slot;     // [nb] position of a source leaf in a compact padded array, -1 for the others
     const int32_t* src_by_level; // [n_src] ids of the source leaves sorted by level
     int64_t n_src;
-    const int32_t* by_kind;      // [nb] first the n_plain blocks without a coarser source, then the others
-    int64_t n_plain;
+    const int32_t* sched;        // [n_sched] launch order of the 24-field kernel, see HostTree::sched
+    int64_t n_sched;
 };
+
+// HostTree::sched is made of chunks of this many entries; the kernels hand one chunk to one XCD
+constexpr int kSchedChunk = 16;
+constexpr int32_t kSchedCoarse = 1 << 30;   // flag on a schedule entry: the block has a coarser source
 
 // how the right-hand side leaves the kernel
 enum Epilogue : int {

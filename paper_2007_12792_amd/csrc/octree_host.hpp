@@ -33,11 +33,12 @@ struct HostTree {
     // src_by_level / src_level_start list them by level like by_level / level_start.
     std::vector<int32_t> src_slot, src_by_level;
     int64_t src_level_start[21] = {};
-    // Block ids split by whether a block takes ghost values from a coarser leaf: first the n_plain blocks
-    // that do not (Morton order), then the others (Morton order).  The 24-field kernel is launched once per
-    // part, so that the part without interpolation is compiled without it.
-    std::vector<int32_t> by_kind;
-    int64_t n_plain = 0;
+    // Launch order of the 24-field kernel.  The blocks are split by whether they take ghost values from a
+    // coarser leaf (those that do not run a path compiled without the interpolation).  Each part, in Morton
+    // order, is cut into chunks of kSchedChunk entries (the last one padded with -1); the chunks of the two
+    // parts are dealt into one sequence in proportion, so that both kinds of work are on the device together
+    // from the first to the last workgroup.  Entry = block id, | kSchedCoarse for the second part.
+    std::vector<int32_t> sched;
 };
 
 // Each returns an OT_* status.

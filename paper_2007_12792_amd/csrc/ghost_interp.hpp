@@ -19,13 +19,16 @@ __device__ __forceinline__ int div_by(int q, uint32_t magic) { return (int)__umu
 // source, and all source leaves of a round are requested from memory together.
 // Staging per round: region A holds the coarse leaves (512 each) and, after the x pass, the y-pass
 // results; region B, behind it, holds the x-pass results.
-// done by one thread per block, once: boxes from the packed region ranges, greedy rounds in list order
-__device__ void make_box_plan(BlockInfo& bi)
+// done by one thread per block, once: boxes from the packed region ranges, greedy rounds in list order.
+// with_corners = false: the sources that cover only a corner of the padded block (last in the list) are
+// left out; the right-hand-side kernels never read the corners.
+__device__ void make_box_plan(BlockInfo& bi, bool with_corners)
 {
     BoxPlan& bp = bi.box;
     int nr = 0, sumc = 0, sum1 = 0, sum2 = 0, sum3 = 0, ns = 0;
+    const int limit = with_corners ? 8 : bi.cs[29];
     bp.rbeg[0] = 0;
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < limit; ++s) {
         if (bi.cs[2 * s] < 0) break;
         const int pk = bi.cs[2 * s + 1];
         const int rxl = pk & 3, rxh = (pk >> 2) & 3, ryl = (pk >> 4) & 3, ryh = (pk >> 6) & 3, rzl = (pk >> 8) & 3, rzh = (pk >> 10) & 3;

@@ -114,7 +114,7 @@ __device__ __forceinline__ void rhs_block(const DeviceTree& tr, const RhsArgs& a
     const int64_t nb = tr.nb;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
-    if (tid == 0 && COARSE && (KIND == OT_RHS_SYN24 || CENTRED)) make_box_plan(bi);   // read only after the next barrier
+    if (tid == 0 && COARSE && (KIND == OT_RHS_SYN24 || CENTRED)) make_box_plan(bi, false);   // read only after the next barrier
 
     int i, j, k;
     point_of(tid, i, j, k);
@@ -317,7 +317,7 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, con
     const int v0 = (int)(blockIdx.x - b * stride);
     load_block_info(bi, tr, b, tid);
     __syncthreads();
-    if (tid == 0) make_box_plan(bi);
+    if (tid == 0) make_box_plan(bi, true);
     FillPlan<PLAN_FULL> fp;
     fp.src = reinterpret_cast<uint32_t*>(scratch);   // the staging area is free until the first interpolation
     make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const
     const int64_t nout = SOURCES ? tr.n_src : nb;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
-    if (tid == 0) make_box_plan(bi);
+    if (tid == 0) make_box_plan(bi, true);
     FillPlan<PLAN_FULL> fp;
     fp.src = reinterpret_cast<uint32_t*>(scratch);   // the staging area is free until the first interpolation
     make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);

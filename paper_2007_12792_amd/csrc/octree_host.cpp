@@ -203,9 +203,19 @@ void make_coarse_sources(HostTree& t)
                 }
             }
         }
-        for (int s = 0; s < n; ++s) {
-            out[2 * s] = ids[s];
-            out[2 * s + 1] = lo[s][0] | (hi[s][0] << 2) | (lo[s][1] << 4) | (hi[s][1] << 6) | (lo[s][2] << 8) | (hi[s][2] << 10);
+        // sources whose box is one corner of the padded block (ghost part on every axis) go last: kernels that
+        // do not read the corners use only the sources in front of them
+        int m = 0;
+        for (int pass = 0; pass < 2; ++pass) {
+            for (int s = 0; s < n; ++s) {
+                const bool corner = lo[s][0] == hi[s][0] && lo[s][0] != 1 && lo[s][1] == hi[s][1] && lo[s][1] != 1 &&
+                                    lo[s][2] == hi[s][2] && lo[s][2] != 1;
+                if (corner != (pass == 1)) continue;
+                out[2 * m] = ids[s];
+                out[2 * m + 1] = lo[s][0] | (hi[s][0] << 2) | (lo[s][1] << 4) | (hi[s][1] << 6) | (lo[s][2] << 8) | (hi[s][2] << 10);
+                ++m;
+            }
+            if (pass == 0) out[29] = m;
         }
     }
 }
@@ -244,7 +254,7 @@ void make_level_lists(HostTree& t)
     // launch order of the 24-field kernel: chunks without / with a coarser source, dealt in proportion
     std::vector<int32_t> part[2];
     for (size_t b = 0; b < nb; ++b) {
-        const bool has = t.coarse[b * kCoarseRow] >= 0;
+        const bool has = t.coarse[b * kCoarseRow + 29] > 0;   // a coarser source that covers more than a corner
         part[has].push_back(static_cast<int32_t>(b) | (has ? kSchedCoarse : 0));
     }
     size_t nchunk[2], done[2] = {0, 0};

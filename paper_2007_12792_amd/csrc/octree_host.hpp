@@ -21,8 +21,10 @@ struct HostTree {
     //            8 x {leaf id, packed ranges}, id -1 ends the list; packed = xlo | xhi<<2 | ylo<<4 |
     //            yhi<<6 | zlo<<8 | zhi<<10 with 0/1/2 naming the ghost-low, interior and ghost-high
     //            part of an axis (inclusive ranges);
+    //            Sources whose box is a single corner of the padded block come last;
     //   [16]     number of face neighbours that are coarser, then [17..28] that many {face, leaf id}
-    //            pairs, face = 2*axis + (0 low side, 1 high side).
+    //            pairs, face = 2*axis + (0 low side, 1 high side);
+    //   [29]     number of sources in front of the corner-only ones.
     std::vector<int32_t> coarse;
     // Block ids sorted by level (ascending, Morton order within a level): blocks of level l are
     // by_level[level_start[l] .. level_start[l+1]).  Used by the level-ordered ghost fill.
@@ -34,7 +36,8 @@ struct HostTree {
     std::vector<int32_t> src_slot, src_by_level;
     int64_t src_level_start[21] = {};
     // Launch order of the 24-field kernel.  The blocks are split by whether they take ghost values from a
-    // coarser leaf (those that do not run a path compiled without the interpolation).  Each part, in Morton
+    // coarser leaf other than into a corner of the padded block, which that kernel does not read (those that
+    // do not run a path compiled without the interpolation).  Each part, in Morton
     // order, is cut into chunks of kSchedChunk entries (the last one padded with -1); the chunks of the two
     // parts are dealt into one sequence in proportion, so that both kinds of work are on the device together
     // from the first to the last workgroup.  Entry = block id, | kSchedCoarse for the second part.

@@ -43,7 +43,8 @@ struct BoxPlan {
 struct BlockInfo {       // per-workgroup copy of the block's table rows
     int32_t gt[27 * 5];
     int32_t cs[32];      // [0..15] coarse sources: {leaf id, packed region range} x 8, id < 0 ends the
-                         // list; [16] number of coarser faces, [17..28] {face, leaf id} pairs
+                         // list, corner-only sources last; [16] number of coarser faces, [17..28] {face, leaf id}
+                         // pairs; [29] number of sources in front of the corner-only ones
     int32_t slot[8];     // centred ghost rule: where the padded block of coarse source s sits (src_slot of its id)
     uint32_t level, ax, ay, az;
     double lag[36];

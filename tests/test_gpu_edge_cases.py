@@ -219,3 +219,32 @@ def test_rk_step_can_be_captured_in_a_graph_and_replayed(dev, name, kind, nsteps
         torch.cuda.synchronize()
         assert torch.equal(ug, eager[n]), "replay %d" % n
         assert np.isfinite((eager[n] * 0.5).sum().item())   # eager work and a synchronisation between replays
+
+
+def test_two_trees_step_concurrently_on_two_streams(dev):  # noqa: F811
+    # calls on different trees may overlap: steps of a wave tree and of a 24-field tree issued alternately on two
+    # streams give the bits of the same steps issued one after the other
+    ta, tb = octfd.Tree.build(**sd.tree_params("T3")), octfd.Tree.build(**sd.tree_params("T4"))
+    ua0 = sd.make_fields("T3", ta.leaves, device=dev)
+    ub0 = sd.make_fields("T4", tb.leaves, device=dev)
+    wa = torch.empty(ta.rk_workspace_bytes(1) // 8, dtype=torch.float64, device=dev)
+    wb = torch.empty(tb.rk_workspace_bytes(3) // 8, dtype=torch.float64, device=dev)
+    dta, dtb = sd.time_step(sd.CONFIGS["T3"]["lmax"]), sd.time_step(sd.CONFIGS["T4"]["lmax"])
+    ua, ub = ua0.clone(), ub0.clone()
+    for _ in range(2):
+        ta.rk_step(1, ua, dta, wa, sigma=sd.KO_SIGMA)
+    for _ in range(2):
+        tb.rk_step(3, ub, dtb, wb, sigma=sd.KO_SIGMA)
+    torch.cuda.synchronize()
+    va, vb = ua0.clone(), ub0.clone()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(2):
+        with torch.cuda.stream(sa):
+            ta.rk_step(1, va, dta, wa, sigma=sd.KO_SIGMA, stream=sa)
+        with torch.cuda.stream(sb):
+            tb.rk_step(3, vb, dtb, wb, sigma=sd.KO_SIGMA, stream=sb)
+    sa.synchronize()
+    sb.synchronize()
+    assert torch.isfinite(va).all() and torch.isfinite(vb).all()
+    assert torch.equal(va, ua) and torch.equal(vb, ub)

@@ -24,6 +24,7 @@ struct DeviceTree {
 
 // HostTree::sched is made of chunks of this many entries; the kernels hand one chunk to one XCD
 constexpr int kSchedChunk = 16;
+constexpr int kSchedXcds = 8;    // XCDs of the device: workgroup i runs on XCD i mod 8
 constexpr int32_t kSchedCoarse = 1 << 30;   // flag on a schedule entry: the block has a coarser source
 
 // how the right-hand side leaves the kernel

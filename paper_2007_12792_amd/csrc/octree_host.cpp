@@ -257,21 +257,23 @@ void make_level_lists(HostTree& t)
         const bool has = t.coarse[b * kCoarseRow + 29] > 0;   // a coarser source that covers more than a corner
         part[has].push_back(static_cast<int32_t>(b) | (has ? kSchedCoarse : 0));
     }
-    size_t nchunk[2], done[2] = {0, 0};
+    // dealt in units of one chunk per XCD, so that every XCD meets the two kinds in the same order
+    constexpr size_t kUnit = static_cast<size_t>(kSchedChunk) * kSchedXcds;
+    size_t nunit[2], done[2] = {0, 0};
     for (int p = 0; p < 2; ++p) {
-        while (part[p].size() % kSchedChunk) part[p].push_back(-1);
-        nchunk[p] = part[p].size() / kSchedChunk;
+        while (part[p].size() % kUnit) part[p].push_back(-1);
+        nunit[p] = part[p].size() / kUnit;
     }
     t.sched.clear();
     t.sched.reserve(part[0].size() + part[1].size());
-    while (done[0] < nchunk[0] || done[1] < nchunk[1]) {
-        // take from the part that is further behind its share (done / nchunk smaller); measured on the
+    while (done[0] < nunit[0] || done[1] < nunit[1]) {
+        // take from the part that is further behind its share (done / nunit smaller); measured on the
         // 102,075-block tree against all chunks of one part first: 75.0 ms per step against 78.4 and 79.2
         int p = 0;
-        if (done[0] >= nchunk[0]) p = 1;
-        else if (done[1] < nchunk[1] && done[1] * nchunk[0] < done[0] * nchunk[1]) p = 1;
-        const int32_t* src = part[p].data() + done[p] * kSchedChunk;
-        t.sched.insert(t.sched.end(), src, src + kSchedChunk);
+        if (done[0] >= nunit[0]) p = 1;
+        else if (done[1] < nunit[1] && done[1] * nunit[0] < done[0] * nunit[1]) p = 1;
+        const int32_t* src = part[p].data() + done[p] * kUnit;
+        t.sched.insert(t.sched.end(), src, src + kUnit);
         ++done[p];
     }
 }

@@ -37,10 +37,11 @@ struct HostTree {
     int64_t src_level_start[21] = {};
     // Launch order of the 24-field kernel.  The blocks are split by whether they take ghost values from a
     // coarser leaf other than into a corner of the padded block, which that kernel does not read (those that
-    // do not run a path compiled without the interpolation).  Each part, in Morton
-    // order, is cut into chunks of kSchedChunk entries (the last one padded with -1); the chunks of the two
-    // parts are dealt into one sequence in proportion, so that both kinds of work are on the device together
-    // from the first to the last workgroup.  Entry = block id, | kSchedCoarse for the second part.
+    // do not run a path compiled without the interpolation).  Each part, in Morton order, is cut into chunks of
+    // kSchedChunk entries and these into units of kSchedXcds chunks (the last unit padded with -1); the units of
+    // the two parts are dealt into one sequence in proportion, so that both kinds of work are on the device
+    // together from the first to the last workgroup and every XCD (which receives every kSchedXcds-th chunk)
+    // meets them in the same order.  Entry = block id, | kSchedCoarse for the second part.
     std::vector<int32_t> sched;
 };
 

@@ -84,7 +84,7 @@ __device__ __forceinline__ void stg(double* base, uint32_t byte_off, double v)
 // through the same L2, while every XCD still sees the same mix of cheap and expensive blocks.
 // (Measured on the 102,075-block tree: 78.0 ms per step against 83.5 ms with one contiguous eighth
 // of the Morton order per XCD and 78.4 ms with no remapping.)
-constexpr int NXCD = 8, XCD_CHUNK = kSchedChunk;
+constexpr int NXCD = kSchedXcds, XCD_CHUNK = kSchedChunk;
 __device__ __forceinline__ int64_t block_of_workgroup(int64_t wg)
 {
     const int64_t x = wg % NXCD, q = wg / NXCD;

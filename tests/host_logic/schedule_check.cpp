@@ -47,23 +47,27 @@ static int check(const HostTree& t)
         if (row[29] != first_corner) return fail("count of the sources that are not corner-only", b);
         n_coarse_kind += row[29] > 0;
     }
-    // schedule: every block once, flag = has such a source, chunks of one kind, padding only at a kind's end
-    if (t.sched.size() % kSchedChunk) return fail("schedule length", -1);
+    // schedule: every block once, flag = has such a source; units of kSchedXcds chunks of one kind (one chunk
+    // per XCD), padding (-1) only at the end of a kind's last unit
+    const size_t unit = static_cast<size_t>(kSchedChunk) * kSchedXcds;
+    if (t.sched.size() % unit) return fail("schedule length", -1);
     std::vector<int> times(nb, 0);
-    long pad[2] = {0, 0}, count[2] = {0, 0}, chunks[2] = {0, 0};
-    for (size_t c = 0; c < t.sched.size() / kSchedChunk; ++c) {
+    long pad[2] = {0, 0}, count[2] = {0, 0}, units[2] = {0, 0};
+    std::vector<int> unit_kind;
+    for (size_t c = 0; c < t.sched.size() / unit; ++c) {
         int kind = -1;
-        for (int i = 0; i < kSchedChunk; ++i) {
-            const int32_t e = t.sched[c * kSchedChunk + i];
+        for (size_t i = 0; i < unit; ++i) {
+            const int32_t e = t.sched[c * unit + i];
             if (e < 0) continue;
             const int k = (e & kSchedCoarse) ? 1 : 0;
-            if (kind >= 0 && k != kind) return fail("a chunk mixes the two kinds", e & ~kSchedCoarse);
+            if (kind >= 0 && k != kind) return fail("a unit mixes the two kinds", e & ~kSchedCoarse);
             kind = k;
         }
-        if (kind < 0) return fail("an empty chunk", -1);
-        ++chunks[kind];
-        for (int i = 0; i < kSchedChunk; ++i) {
-            const int32_t e = t.sched[c * kSchedChunk + i];
+        if (kind < 0) return fail("an empty unit", -1);
+        unit_kind.push_back(kind);
+        ++units[kind];
+        for (size_t i = 0; i < unit; ++i) {
+            const int32_t e = t.sched[c * unit + i];
             if (e < 0) { ++pad[kind]; continue; }
             if (pad[kind]) return fail("padding before the end of a kind", e & ~kSchedCoarse);
             const long b = e & ~kSchedCoarse;
@@ -75,19 +79,29 @@ static int check(const HostTree& t)
     }
     for (long b = 0; b < nb; ++b)
         if (times[b] != 1) return fail("a block is not scheduled exactly once", b);
-    if (count[1] != n_coarse_kind || pad[0] >= kSchedChunk || pad[1] >= kSchedChunk) return fail("counts", -1);
-    // dealt in proportion: after every chunk the two kinds are within one chunk of their shares
-    long done[2] = {0, 0};
-    for (size_t c = 0; c < t.sched.size() / kSchedChunk; ++c) {
-        int32_t e = -1;
-        for (int i = 0; i < kSchedChunk && e < 0; ++i) e = t.sched[c * kSchedChunk + i];
-        ++done[(e & kSchedCoarse) ? 1 : 0];
-        if (chunks[0] && chunks[1]) {
-            const double lag = std::fabs(static_cast<double>(done[0]) / chunks[0] - static_cast<double>(done[1]) / chunks[1]);
-            if (lag > 1.0 / chunks[0] + 1.0 / chunks[1] + 1e-12) return fail("the kinds drift apart in the schedule", static_cast<long>(c));
+    if (count[1] != n_coarse_kind || pad[0] >= static_cast<long>(unit) || pad[1] >= static_cast<long>(unit)) return fail("counts", -1);
+    // within a kind the blocks keep their (Morton) order
+    {
+        long last[2] = {-1, -1};
+        for (int32_t e : t.sched) {
+            if (e < 0) continue;
+            const int k = (e & kSchedCoarse) ? 1 : 0;
+            const long b = e & ~kSchedCoarse;
+            if (b <= last[k]) return fail("order within a kind", b);
+            last[k] = b;
         }
     }
-    std::printf("blocks %ld, with a coarser source beyond a corner %ld, chunks %ld + %ld\n", nb, n_coarse_kind, chunks[0], chunks[1]);
+    // dealt in proportion: after every unit the two kinds are within one unit of their shares
+    long done[2] = {0, 0};
+    for (size_t c = 0; c < unit_kind.size(); ++c) {
+        ++done[unit_kind[c]];
+        if (units[0] && units[1]) {
+            const double lag = std::fabs(static_cast<double>(done[0]) / units[0] - static_cast<double>(done[1]) / units[1]);
+            if (lag > 1.0 / units[0] + 1.0 / units[1] + 1e-12) return fail("the kinds drift apart in the schedule", static_cast<long>(c));
+        }
+    }
+    const long* chunks = units;
+    std::printf("blocks %ld, with a coarser source beyond a corner %ld, units %ld + %ld\n", nb, n_coarse_kind, chunks[0], chunks[1]);
     return 0;
 }
 

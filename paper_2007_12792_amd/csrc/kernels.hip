@@ -97,205 +97,202 @@ struct RhsLds {
     static constexpr int NPLAN_SRC = PLAN_IN_REGS ? 1 : NPLAN * NTHREADS;
 };
 
-// One block, all its variables: the whole right-hand side (and Runge-Kutta stage update) of block b.
-// COARSE = false promises that b has no coarser source: no box plan, no interpolation code (for the
-// 24-field kernel that is 2 spilled registers instead of 11, and 5 % less time on a uniform tree).
-// The LDS arrays belong to the calling kernel (sizes: RhsLds).
-template <int KIND, bool ZIN, int EPI, bool CENTRED, bool COARSE>
-__device__ __forceinline__ void rhs_block(const DeviceTree& tr, const RhsArgs& a, const int64_t b, double* tiles, double* scratch,
-                                          BlockInfo& bi, uint32_t* plan_src)
-{
-    static_assert(COARSE || !CENTRED, "the ghost rules differ only where a coarser source exists");
-    static_assert(ZIN || !CENTRED, "the centred ghost rule applies to zipped input");
-    constexpr int NPLAN = RhsLds<KIND, ZIN>::NPLAN, NPOINTS = RhsLds<KIND, ZIN>::NPOINTS;
-    constexpr bool PLAN_IN_REGS = RhsLds<KIND, ZIN>::PLAN_IN_REGS;
-
-    const int tid = threadIdx.x;
-    const int64_t nb = tr.nb;
-    load_block_info(bi, tr, b, tid);
-    __syncthreads();
-    if (tid == 0 && COARSE && (KIND == OT_RHS_SYN24 || CENTRED)) make_box_plan(bi, false);   // read only after the next barrier
-
-    int i, j, k;
-    point_of(tid, i, j, k);
-    const int c = tidx(k + PAD, j + PAD, i + PAD);
-    // byte offsets of this thread's point inside one variable's zipped array / inside a padded block
-    const uint32_t o8 = ((uint32_t)b * BLK + (k * NPT + j) * NPT + i) * 8u;
-    const uint32_t p8 = (((k + PAD) * NP + (j + PAD)) * NP + (i + PAD)) * 8u;
-    const double ih = (double)(NPT << bi.level), ih2 = ih * ih;
-    const double sigma = a.sigma;
-
-    FillPlan<NPLAN, PLAN_IN_REGS> fp;
-    fp.src = plan_src;
-    if (ZIN) make_plan_zipped<NPLAN, NPOINTS>(fp, bi, tid);
-    else make_plan_padded<NPLAN, NPOINTS>(fp, tid);
-    double pv[NPLAN];
-    double cv[CPRE];   // values of coarser face neighbours requested ahead (SYN24 first-derivative passes)
-
-    auto var_base = [&](int v) -> const double* {
-        return ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK;
-    };
-    auto pad_base = [&](int v) -> const double* {   // centred rule: variable v's padded source leaves
-        return CENTRED ? a.pad_src + (int64_t)v * tr.n_src * PBLK : nullptr;
-    };
-    auto stage = [&](int v) {   // bring variable v into tile buffer 0 (barrier before and after)
-        __syncthreads();
-        prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(v), tid);
-        commit<ZIN, NPLAN, PLAN_FACE, CENTRED, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(v), tid, pad_base(v));
-        __syncthreads();
-    };
-    auto centre = [&](int v) -> double {   // this thread's own value of variable v
-        return ZIN ? ldg(a.in + (int64_t)v * nb * BLK, o8) : ldg(a.in + ((int64_t)v * nb + b) * PBLK, p8);
-    };
-
-    if (KIND == OT_RHS_DERIVS) {
-        stage(0);
-        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
-        const EpiOperands e2 = epi_prefetch<EPI>(a, nb, 2, o8), e3 = epi_prefetch<EPI>(a, nb, 3, o8);
-        const PointOps p = point_ops<true>(tiles, c, 0.0, ih, ih2);
-        emit<EPI>(a, nb, 0, b, o8, p8, p.dx, e0);
-        emit<EPI>(a, nb, 1, b, o8, p8, p.dy, e1);
-        emit<EPI>(a, nb, 2, b, o8, p8, p.dz, e2);
-        emit<EPI>(a, nb, 3, b, o8, p8, p.lap, e3);
-    } else if (KIND == OT_RHS_WAVE) {
-        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
-        stage(0);
-        prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(1), tid);   // pi is on its way while u is differentiated
-        const PointOps pu = point_ops<true>(tiles, c, sigma, ih, ih2);
-        __syncthreads();
-        commit<ZIN, NPLAN, PLAN_FACE, CENTRED, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(1), tid, pad_base(1));
-        __syncthreads();
-        const PointOps pp = point_ops<false>(tiles, c, sigma, ih, ih2);
-        emit<EPI>(a, nb, 0, b, o8, p8, pp.u0 + pu.ko, e0);
-        emit<EPI>(a, nb, 1, b, o8, p8, pu.lap + pp.ko, e1);
-    } else if (KIND == OT_RHS_BURGERS) {
-        stage(0);
-        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8);
-        const PointOps p = point_ops<false>(tiles, c, sigma, ih, ih2);
-        const double flux = p.u0 * p.dx;
-        emit<EPI>(a, nb, 0, b, o8, p8, p.ko - flux, e0);
-    } else {
-        // SYN24.  The variables are streamed in descending cyclic order (see syn24_stream).  The
-        // first ten real passes (variables 9..0) evaluate the second-derivative combinations Lap_s;
-        // each thread parks them at its own point in variables 10+s of the `stash` array, from where
-        // the later passes (variables 23..10, which need Lap_{a mod 10}) read them back before those
-        // slots receive their final values.  Per-thread state thus shrinks to one gradient.
-        //
-        // The tile is double-buffered and global memory is requested ahead of its use: tile data
-        // of the next variable is loaded into registers at the top of a pass and committed to the
-        // other LDS buffer at its end (one barrier per pass, plus the one inside mixed_derivs); the
-        // pointwise operands of the next pass (RK accumulator and state, u_{a+11}, Lap) likewise.
-        double* wz = scratch;
-        double* wy = scratch + WZ;
-        const double halpha = 0.5 * centre(0), bx = centre(1), by = centre(2), bz = centre(3);
-        const double Gxx = 1.0 - 0.125 * centre(4), Gxy = -(0.125 * centre(5)), Gxz = -(0.125 * centre(6));
-        const double Gyy = 1.0 - 0.125 * centre(7), Gyz = -(0.125 * centre(8)), Gzz = 1.0 - 0.125 * centre(9);
-        double nx = 0, ny = 0, nz = 0;
-        const int ownz = k * PS + (j + PAD) * RS + (i + PAD), owny = k * YPS + j * RS + (i + PAD);
-        struct Look { double unext, lap; EpiOperands eo; };
-
-        auto stash_base = [&](int v) -> double* {   // where Lap_{v-10} is parked (v = 10..19)
-            return EPI == kOutPadded ? a.stash + ((int64_t)v * nb + b) * PBLK : a.stash + (int64_t)v * nb * BLK;
-        };
-        const uint32_t s8 = EPI == kOutPadded ? p8 : o8;
-
-        // top of pass t: request the tile data of pass t+1 and this pass's own pointwise operands.
-        // NEXT_USE says how much of the tile pass t+1 reads (edges only if it takes second derivatives).
-        auto issue = [&](int t, int f, Look& l, int& f1, auto next_use) {
-            constexpr int NEXT_USE = decltype(next_use)::value;
-            if (t + 1 < NSTREAM) {
-                f1 = syn24_stream(t + 1);
-                prefetch<NPLAN, NEXT_USE>(pv, fp, var_base(f1), tid);
-                if (ZIN && COARSE && !CENTRED && NEXT_USE == PLAN_FACE) coarse_prefetch(cv, bi, var_base(f1), tid);
-            }
-            l.unext = centre((f + 11) % 24);
-            l.eo = epi_prefetch<EPI>(a, nb, f, o8);
-            if (t > 10) l.lap = ldg(stash_base(10 + f % 10), s8);
-        };
-        using UseEdge = std::integral_constant<int, PLAN_EDGE>;
-        using UseFace = std::integral_constant<int, PLAN_FACE>;
-        // pass over a variable with second derivatives (9..0)
-        auto pass_d2 = [&](int t, auto next_use) {
-            constexpr int NEXT_USE = decltype(next_use)::value;
-            const double* T = tiles + (t & 1) * TILE;
-            const int f = syn24_stream(t);
-            int f1 = 0;
-            Look l{0.0, 0.0, {0.0, 0.0}};
-            issue(t, f, l, f1, next_use);
-            const Syn24Part p = syn24_axes<true>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
-            const Mixed mx = mixed_derivs(T, wy, wz, tid, owny, ownz, ih);
-            double off = Gxy * mx.dxy;
-            off = fma(Gxz, mx.dxz, off);
-            off = fma(Gyz, mx.dyz, off);
-            const double lap = fma(2.0, off, p.diag);
-            stg(stash_base(10 + f), s8, lap);
-            emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l.unext), l.eo);
-            commit<ZIN, NPLAN, NEXT_USE, CENTRED, COARSE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, NEXT_USE == PLAN_FACE, var_base(f1), tid, pad_base(f1));
-            __syncthreads();
-        };
-        // pass over a variable without second derivatives (23..10)
-        auto pass_light = [&](int t) {
-            const double* T = tiles + (t & 1) * TILE;
-            const int f = syn24_stream(t);
-            int f1 = 0;
-            Look l{0.0, 0.0, {0.0, 0.0}};
-            issue(t, f, l, f1, UseFace{});
-            const Syn24Part p = syn24_axes<false>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
-            emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, l.lap, halpha, l.unext), l.eo);
-            if (t + 1 < NSTREAM) {
-                commit<ZIN, NPLAN, PLAN_FACE, CENTRED, COARSE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, true, var_base(f1), tid, pad_base(f1));
-                __syncthreads();
-            }
-        };
-
-        {   // pass 0: gradient of variable 10 only
-            const int f = syn24_stream(0), f1 = syn24_stream(1);
-            prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(f), tid);
-            if (CENTRED) __syncthreads();            // the box plan, made by one thread, is read in this commit already
-            commit<ZIN, NPLAN, PLAN_FACE, CENTRED, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(f), tid, pad_base(f));
-            __syncthreads();
-            prefetch<NPLAN, PLAN_EDGE>(pv, fp, var_base(f1), tid);
-            nx = d1_at(tiles, c, 1, ih); ny = d1_at(tiles, c, RS, ih); nz = d1_at(tiles, c, PS, ih);
-            commit<ZIN, NPLAN, PLAN_EDGE, CENTRED, COARSE>(tiles + TILE, scratch, bi, fp, pv, cv, false, var_base(f1), tid, pad_base(f1));
-            __syncthreads();
-        }
-#pragma unroll 1
-        for (int t = 1; t < 10; ++t) pass_d2(t, UseEdge{});
-        pass_d2(10, UseFace{});
-#pragma unroll 1
-        for (int t = 11; t < NSTREAM; ++t) pass_light(t);
-    }
-}
-
-template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
+// The right-hand side (and Runge-Kutta stage update) of whole blocks, one block per workgroup, all its variables.
+// SCHED = false: block = position of the workgroup.  SCHED = true (24-field system): the workgroup takes its block
+// from the tree's schedule (see HostTree::sched), in which chunks of blocks without a coarser source are dealt in
+// among chunks of blocks with one; the former run the body compiled with COARSE = false: no box plan, no
+// interpolation code (2 spilled registers instead of 11, and 5 % less time on a uniform tree).
+// The body is a generic lambda inside the kernel, so that it names the LDS arrays directly in both instances.
+template <int KIND, bool ZIN, int EPI, bool CENTRED = false, bool SCHED = false>
 __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTree tr, RhsArgs a)
 {
+    static_assert(ZIN || !CENTRED, "the centred ghost rule applies to zipped input");
+    static_assert(ZIN || !SCHED, "the schedule is for zipped input");
     using L = RhsLds<KIND, ZIN>;
     __shared__ double tiles[L::NBUF * TILE];
     __shared__ double scratch[L::NSCRATCH];
     __shared__ BlockInfo bi;
     __shared__ uint32_t plan_src[L::NPLAN_SRC];
-    const int64_t b = block_of_workgroup(blockIdx.x);
-    if (b >= tr.nb) return;                          // uniform over the workgroup
-    rhs_block<KIND, ZIN, EPI, CENTRED, true>(tr, a, b, tiles, scratch, bi, plan_src);
-}
+    constexpr int NPLAN = L::NPLAN, NPOINTS = L::NPOINTS;
+    constexpr bool PLAN_IN_REGS = L::PLAN_IN_REGS;
 
-// The same over the tree's schedule (see HostTree::sched): chunks of blocks without a coarser source, which take
-// the path compiled without interpolation, dealt in among chunks of blocks with one.
-template <int KIND, int EPI, bool CENTRED = false>
-__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs_sched(DeviceTree tr, RhsArgs a)
-{
-    using L = RhsLds<KIND, true>;
-    __shared__ double tiles[L::NBUF * TILE];
-    __shared__ double scratch[L::NSCRATCH];
-    __shared__ BlockInfo bi;
-    __shared__ uint32_t plan_src[L::NPLAN_SRC];
+    auto block = [&](const int64_t b, auto coarse_tag) {
+        constexpr bool COARSE = decltype(coarse_tag)::value;
+        constexpr bool CEN = CENTRED && COARSE;      // the ghost rules differ only where a coarser source exists
+
+        const int tid = threadIdx.x;
+        const int64_t nb = tr.nb;
+        load_block_info(bi, tr, b, tid);
+        __syncthreads();
+        if (tid == 0 && COARSE && (KIND == OT_RHS_SYN24 || CEN)) make_box_plan(bi, false);   // read only after the next barrier
+
+        int i, j, k;
+        point_of(tid, i, j, k);
+        const int c = tidx(k + PAD, j + PAD, i + PAD);
+        // byte offsets of this thread's point inside one variable's zipped array / inside a padded block
+        const uint32_t o8 = ((uint32_t)b * BLK + (k * NPT + j) * NPT + i) * 8u;
+        const uint32_t p8 = (((k + PAD) * NP + (j + PAD)) * NP + (i + PAD)) * 8u;
+        const double ih = (double)(NPT << bi.level), ih2 = ih * ih;
+        const double sigma = a.sigma;
+
+        FillPlan<NPLAN, PLAN_IN_REGS> fp;
+        fp.src = plan_src;
+        if (ZIN) make_plan_zipped<NPLAN, NPOINTS>(fp, bi, tid);
+        else make_plan_padded<NPLAN, NPOINTS>(fp, tid);
+        double pv[NPLAN];
+        double cv[CPRE];   // values of coarser face neighbours requested ahead (SYN24 first-derivative passes)
+
+        auto var_base = [&](int v) -> const double* {
+            return ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK;
+        };
+        auto pad_base = [&](int v) -> const double* {   // centred rule: variable v's padded source leaves
+            return CEN ? a.pad_src + (int64_t)v * tr.n_src * PBLK : nullptr;
+        };
+        auto stage = [&](int v) {   // bring variable v into tile buffer 0 (barrier before and after)
+            __syncthreads();
+            prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(v), tid);
+            commit<ZIN, NPLAN, PLAN_FACE, CEN, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(v), tid, pad_base(v));
+            __syncthreads();
+        };
+        auto centre = [&](int v) -> double {   // this thread's own value of variable v
+            return ZIN ? ldg(a.in + (int64_t)v * nb * BLK, o8) : ldg(a.in + ((int64_t)v * nb + b) * PBLK, p8);
+        };
+
+        if (KIND == OT_RHS_DERIVS) {
+            stage(0);
+            const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
+            const EpiOperands e2 = epi_prefetch<EPI>(a, nb, 2, o8), e3 = epi_prefetch<EPI>(a, nb, 3, o8);
+            const PointOps p = point_ops<true>(tiles, c, 0.0, ih, ih2);
+            emit<EPI>(a, nb, 0, b, o8, p8, p.dx, e0);
+            emit<EPI>(a, nb, 1, b, o8, p8, p.dy, e1);
+            emit<EPI>(a, nb, 2, b, o8, p8, p.dz, e2);
+            emit<EPI>(a, nb, 3, b, o8, p8, p.lap, e3);
+        } else if (KIND == OT_RHS_WAVE) {
+            stage(0);
+            prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(1), tid);   // pi is on its way while u is differentiated
+            const PointOps pu = point_ops<true>(tiles, c, sigma, ih, ih2);
+            // the operands of the stage update are requested only now: four more values live during the stencils
+            // above push the kernel over the 64 registers that let four workgroups share a compute unit, and a
+            // kernel that spills there loses a quarter of its speed (the fence keeps the scheduler from moving the
+            // loads back up)
+            __syncthreads();
+            commit<ZIN, NPLAN, PLAN_FACE, CEN, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(1), tid, pad_base(1));
+            __builtin_amdgcn_sched_barrier(0);
+            const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
+            __syncthreads();
+            const PointOps pp = point_ops<false>(tiles, c, sigma, ih, ih2);
+            emit<EPI>(a, nb, 0, b, o8, p8, pp.u0 + pu.ko, e0);
+            emit<EPI>(a, nb, 1, b, o8, p8, pu.lap + pp.ko, e1);
+        } else if (KIND == OT_RHS_BURGERS) {
+            stage(0);
+            const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8);
+            const PointOps p = point_ops<false>(tiles, c, sigma, ih, ih2);
+            const double flux = p.u0 * p.dx;
+            emit<EPI>(a, nb, 0, b, o8, p8, p.ko - flux, e0);
+        } else {
+            // SYN24.  The variables are streamed in descending cyclic order (see syn24_stream).  The
+            // first ten real passes (variables 9..0) evaluate the second-derivative combinations Lap_s;
+            // each thread parks them at its own point in variables 10+s of the `stash` array, from where
+            // the later passes (variables 23..10, which need Lap_{a mod 10}) read them back before those
+            // slots receive their final values.  Per-thread state thus shrinks to one gradient.
+            //
+            // The tile is double-buffered and global memory is requested ahead of its use: tile data
+            // of the next variable is loaded into registers at the top of a pass and committed to the
+            // other LDS buffer at its end (one barrier per pass, plus the one inside mixed_derivs); the
+            // pointwise operands of the next pass (RK accumulator and state, u_{a+11}, Lap) likewise.
+            double* wz = scratch;
+            double* wy = scratch + WZ;
+            const double halpha = 0.5 * centre(0), bx = centre(1), by = centre(2), bz = centre(3);
+            const double Gxx = 1.0 - 0.125 * centre(4), Gxy = -(0.125 * centre(5)), Gxz = -(0.125 * centre(6));
+            const double Gyy = 1.0 - 0.125 * centre(7), Gyz = -(0.125 * centre(8)), Gzz = 1.0 - 0.125 * centre(9);
+            double nx = 0, ny = 0, nz = 0;
+            const int ownz = k * PS + (j + PAD) * RS + (i + PAD), owny = k * YPS + j * RS + (i + PAD);
+            struct Look { double unext, lap; EpiOperands eo; };
+
+            auto stash_base = [&](int v) -> double* {   // where Lap_{v-10} is parked (v = 10..19)
+                return EPI == kOutPadded ? a.stash + ((int64_t)v * nb + b) * PBLK : a.stash + (int64_t)v * nb * BLK;
+            };
+            const uint32_t s8 = EPI == kOutPadded ? p8 : o8;
+
+            // top of pass t: request the tile data of pass t+1 and this pass's own pointwise operands.
+            // NEXT_USE says how much of the tile pass t+1 reads (edges only if it takes second derivatives).
+            auto issue = [&](int t, int f, Look& l, int& f1, auto next_use) {
+                constexpr int NEXT_USE = decltype(next_use)::value;
+                if (t + 1 < NSTREAM) {
+                    f1 = syn24_stream(t + 1);
+                    prefetch<NPLAN, NEXT_USE>(pv, fp, var_base(f1), tid);
+                    if (ZIN && COARSE && !CEN && NEXT_USE == PLAN_FACE) coarse_prefetch(cv, bi, var_base(f1), tid);
+                }
+                l.unext = centre((f + 11) % 24);
+                l.eo = epi_prefetch<EPI>(a, nb, f, o8);
+                if (t > 10) l.lap = ldg(stash_base(10 + f % 10), s8);
+            };
+            using UseEdge = std::integral_constant<int, PLAN_EDGE>;
+            using UseFace = std::integral_constant<int, PLAN_FACE>;
+            // pass over a variable with second derivatives (9..0)
+            auto pass_d2 = [&](int t, auto next_use) {
+                constexpr int NEXT_USE = decltype(next_use)::value;
+                const double* T = tiles + (t & 1) * TILE;
+                const int f = syn24_stream(t);
+                int f1 = 0;
+                Look l{0.0, 0.0, {0.0, 0.0}};
+                issue(t, f, l, f1, next_use);
+                const Syn24Part p = syn24_axes<true>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
+                const Mixed mx = mixed_derivs(T, wy, wz, tid, owny, ownz, ih);
+                double off = Gxy * mx.dxy;
+                off = fma(Gxz, mx.dxz, off);
+                off = fma(Gyz, mx.dyz, off);
+                const double lap = fma(2.0, off, p.diag);
+                stg(stash_base(10 + f), s8, lap);
+                emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l.unext), l.eo);
+                commit<ZIN, NPLAN, NEXT_USE, CEN, COARSE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, NEXT_USE == PLAN_FACE, var_base(f1), tid, pad_base(f1));
+                __syncthreads();
+            };
+            // pass over a variable without second derivatives (23..10)
+            auto pass_light = [&](int t) {
+                const double* T = tiles + (t & 1) * TILE;
+                const int f = syn24_stream(t);
+                int f1 = 0;
+                Look l{0.0, 0.0, {0.0, 0.0}};
+                issue(t, f, l, f1, UseFace{});
+                const Syn24Part p = syn24_axes<false>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
+                emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, l.lap, halpha, l.unext), l.eo);
+                if (t + 1 < NSTREAM) {
+                    commit<ZIN, NPLAN, PLAN_FACE, CEN, COARSE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, true, var_base(f1), tid, pad_base(f1));
+                    __syncthreads();
+                }
+            };
+
+            {   // pass 0: gradient of variable 10 only
+                const int f = syn24_stream(0), f1 = syn24_stream(1);
+                prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(f), tid);
+                if (CEN) __syncthreads();            // the box plan, made by one thread, is read in this commit already
+                commit<ZIN, NPLAN, PLAN_FACE, CEN, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(f), tid, pad_base(f));
+                __syncthreads();
+                prefetch<NPLAN, PLAN_EDGE>(pv, fp, var_base(f1), tid);
+                nx = d1_at(tiles, c, 1, ih); ny = d1_at(tiles, c, RS, ih); nz = d1_at(tiles, c, PS, ih);
+                commit<ZIN, NPLAN, PLAN_EDGE, CEN, COARSE>(tiles + TILE, scratch, bi, fp, pv, cv, false, var_base(f1), tid, pad_base(f1));
+                __syncthreads();
+            }
+    #pragma unroll 1
+            for (int t = 1; t < 10; ++t) pass_d2(t, UseEdge{});
+            pass_d2(10, UseFace{});
+    #pragma unroll 1
+            for (int t = 11; t < NSTREAM; ++t) pass_light(t);
+        }
+    };
+
     const int64_t q = block_of_workgroup(blockIdx.x);
-    if (q >= tr.n_sched) return;                     // uniform over the workgroup, like everything below
-    const int32_t e = tr.sched[q];
-    if (e < 0) return;                               // padding of a chunk
-    if (e & kSchedCoarse) rhs_block<KIND, true, EPI, CENTRED, true>(tr, a, e & ~kSchedCoarse, tiles, scratch, bi, plan_src);
-    else rhs_block<KIND, true, EPI, false, false>(tr, a, e, tiles, scratch, bi, plan_src);
+    if constexpr (!SCHED) {
+        if (q >= tr.nb) return;                      // uniform over the workgroup, like everything below
+        block(q, std::true_type{});
+    } else {
+        if (q >= tr.n_sched) return;
+        const int32_t e = tr.sched[q];
+        if (e < 0) return;                           // padding of a unit
+        if (e & kSchedCoarse) block(e & ~kSchedCoarse, std::true_type{});
+        else block(e, std::false_type{});
+    }
 }
 
 // ---------------------------------------------------------------- unzip / zip kernels
@@ -419,9 +416,9 @@ template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
 hipError_t launch_one(const DeviceTree& t, const RhsArgs& a, hipStream_t s)
 {
     if constexpr (KIND == OT_RHS_SYN24 && ZIN)
-        hipLaunchKernelGGL((k_rhs_sched<KIND, EPI, CENTRED>), dim3(grid_for_blocks(t.n_sched)), dim3(NTHREADS), 0, s, t, a);
+        hipLaunchKernelGGL((k_rhs<KIND, true, EPI, CENTRED, true>), dim3(grid_for_blocks(t.n_sched)), dim3(NTHREADS), 0, s, t, a);
     else
-        hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, CENTRED>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
+        hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, CENTRED, false>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
     return hipGetLastError();
 }
 

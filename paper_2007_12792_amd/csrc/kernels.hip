@@ -104,7 +104,7 @@ struct RhsLds {
 // interpolation code (2 spilled registers instead of 11, and 5 % less time on a uniform tree).
 // The body is a generic lambda inside the kernel, so that it names the LDS arrays directly in both instances.
 template <int KIND, bool ZIN, int EPI, bool CENTRED = false, bool SCHED = false>
-__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTree tr, RhsArgs a)
+__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND, CENTRED)) void k_rhs(DeviceTree tr, RhsArgs a)
 {
     static_assert(ZIN || !CENTRED, "the centred ghost rule applies to zipped input");
     static_assert(ZIN || !SCHED, "the schedule is for zipped input");

@@ -17,8 +17,10 @@ constexpr int K_COARSER = 2, K_SAME = 0;
 // (i, k): the eight x-contiguous values of four consecutive k planes then fall into 32 different
 // 8-byte banks, and shifting the access by any stencil offset keeps that property.
 // wavefronts per SIMD the right-hand-side kernels are compiled for: the 24-field kernel 4 (128 VGPRs per lane, two
-// workgroups share a compute unit, which is also what its LDS allows); the other kinds 8 (64 VGPRs, four workgroups)
-constexpr int waves_per_simd(int kind) { return kind == OT_RHS_SYN24 ? 4 : 8; }
+// workgroups share a compute unit, which is also what its LDS allows); the other kinds 8 (64 VGPRs, four workgroups),
+// except with the centred ghost rule, whose interpolation does not fit 64 registers without spilling (6: 80 VGPRs,
+// three workgroups; a kernel of this size that spills is slower than one with fewer workgroups)
+constexpr int waves_per_simd(int kind, bool centred) { return kind == OT_RHS_SYN24 ? 4 : (centred ? 6 : 8); }
 constexpr int RS = NP;                   // 14
 constexpr int PS = NP * RS + 4;          // 200
 constexpr int TILE = NP * PS;            // 14 planes

@@ -132,7 +132,10 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND, CENTRED)) void k_rhs
         // byte offsets of this thread's point inside one variable's zipped array / inside a padded block
         const uint32_t o8 = ((uint32_t)b * BLK + (k * NPT + j) * NPT + i) * 8u;
         const uint32_t p8 = (((k + PAD) * NP + (j + PAD)) * NP + (i + PAD)) * 8u;
-        const double ih = (double)(NPT << bi.level), ih2 = ih * ih;
+        // 1/h = 2^(l+3) and 1/h^2, built from the level as bit patterns in scalar registers (the level is the same
+        // for the whole workgroup, which the compiler cannot see through the LDS copy)
+        const int lvl = __builtin_amdgcn_readfirstlane((int)bi.level);
+        const double ih = __longlong_as_double((long long)(1026 + lvl) << 52), ih2 = __longlong_as_double((long long)(1029 + 2 * lvl) << 52);
         const double sigma = a.sigma;
 
         FillPlan<NPLAN, PLAN_IN_REGS> fp;

@@ -60,7 +60,7 @@ __device__ __forceinline__ Syn24Part syn24_axes(const double* t, int c, double* 
     r.t3q = fma(z.d1, nz, r.t3q);
     nz = z.d1;
     if (WITH_D2) { r.diag = fma(Gzz, z.d2, r.diag); wz[ownz] = z.d1; }
-    r.ko = sigma * ((ksum + z.ko) * (ih * 0.015625));
+    r.ko = sigma * ((ksum + z.ko) * over64(ih));
     __builtin_amdgcn_sched_barrier(0);
     return r;
 }

@@ -8,6 +8,10 @@ namespace {
 
 // ---------------------------------------------------------------- stencils on the LDS tile
 
+// x / 64 for a normal x >= 2^-1016 (here: 1/h = 2^(l+3)), done on the exponent bits: the same value as x * 0.015625,
+// but integer arithmetic, which stays in scalar registers when x is uniform over the workgroup
+__device__ __forceinline__ double over64(double x) { return __longlong_as_double(__double_as_longlong(x) - (6LL << 52)); }
+
 constexpr double C60 = 0x1.1111111111111p-6;   // 1/60
 constexpr double C180 = 0x1.6c16c16c16c17p-8;  // 1/180
 
@@ -70,7 +74,7 @@ __device__ __forceinline__ PointOps point_ops(const double* t, int c, double sig
     const AxisOps z = axis_ops<WITH_D2>(t, c, PS, r.u0, ih, ih2);
     r.dz = z.d1; r.dzz = z.d2;
     r.lap = lxy + z.d2;
-    r.ko = sigma * ((kxy + z.ko) * (ih * 0.015625));
+    r.ko = sigma * ((kxy + z.ko) * over64(ih));
     __builtin_amdgcn_sched_barrier(0);
     return r;
 }

@@ -248,3 +248,24 @@ def test_two_trees_step_concurrently_on_two_streams(dev):  # noqa: F811
     sb.synchronize()
     assert torch.isfinite(va).all() and torch.isfinite(vb).all()
     assert torch.equal(va, ua) and torch.equal(vb, ub)
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13, 14, 15, 16])
+def test_random_trees_24_field_right_hand_side(orc, dev, seed):  # noqa: F811
+    # random refinement centres, radii and depths: many shapes of level jumps (one to seven coarser sources per
+    # block, corner-only sources, units of the launch schedule that are mostly padding), every value compared
+    rng = np.random.default_rng(seed)
+    lmax = int(rng.integers(4, 7))
+    npts = int(rng.integers(1, 4))
+    pts = rng.integers(0, 1 << 20, size=(npts, 3)).astype(np.uint32)
+    rad = rng.integers(20000, 140000, size=lmax - 3).astype(np.uint32)
+    to = orc.Tree.build(3, lmax, pts, rad)
+    tg = octfd.Tree.build(3, lmax, pts, rad)
+    assert to.n == tg.n and to.n < 30000
+    u = rng.standard_normal((24, to.n, 8, 8, 8))
+    want = to.F(3, u, sigma=0.4)
+    out = torch.full((24, to.n, 8, 8, 8), float("nan"), dtype=torch.float64, device=dev)
+    tg.rhs_eval_zipped(3, torch.from_numpy(u).to(dev), out, sigma=0.4)
+    got = out.cpu().numpy()
+    print("seed %d: %d blocks, levels 3..%d, %d values differ" % (seed, to.n, lmax, int((got != want).sum())), flush=True)
+    assert_close(got, want, "random tree %d" % seed)

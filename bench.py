@@ -107,8 +107,8 @@ def other_kernels(args, cfg, kind, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C5", help="workload name from synthdata.CONFIGS (default: the headline one)")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--region", choices=("auto", "rk", "rhs"), default="auto",

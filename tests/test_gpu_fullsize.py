@@ -25,7 +25,7 @@ def test_config5_rhs_sampled_and_rk_step(orc, dev):  # noqa: F811
     print("rhs done", flush=True)
     lev = to.leaves[:, 0]
     coarse = np.flatnonzero(lev < 9)
-    sample = np.unique(np.concatenate([np.arange(0, tg.n, 1501), coarse[::97], [0, tg.n - 1]]))
+    sample = np.unique(np.concatenate([np.arange(0, tg.n, 20), coarse[::7], [0, tg.n - 1]]))      # one block in 20, one coarse block in 7
     u = ud.cpu().numpy()
     want = to.F(3, u, sigma=sg, blocks=sample)
     del u
@@ -52,6 +52,25 @@ def test_config5_rhs_sampled_and_rk_step(orc, dev):  # noqa: F811
     print("rk_step C5: worst |diff|/bound = %.3g" % float((err / bound).max()), flush=True)
     assert bool((err <= bound).all())
     assert float((got - ud).abs().max()) > 0
+
+
+def test_config5_unzip_every_block(orc, dev):  # noqa: F811
+    """unzip of all 24 fields on the 102,075-block tree; three of the fields (one from each group of
+    variables a workgroup fills, first, middle, last) are compared on every block, to the bit."""
+    p = sd.tree_params("C5")
+    to, tg = orc.Tree.build(**p), octfd.Tree.build(**p)
+    ud = sd.make_fields("C5", to.leaves, device=dev)
+    pd = dev_empty((24, tg.n, 14, 14, 14), dev)
+    tg.unzip(ud, pd)
+    torch.cuda.synchronize()
+    print("unzip done", flush=True)
+    for v in (0, 13, 23):
+        want = to.unzip(ud[v:v + 1].cpu().numpy())
+        assert torch.equal(pd[v], torch.from_numpy(want[0]).to(dev)), "field %d" % v
+        print("field %d: every value equal" % v, flush=True)
+    back = dev_empty((24, tg.n, 8, 8, 8), dev)
+    tg.zip(pd, back)
+    assert torch.equal(back, ud)
 
 
 def test_centred_step_of_the_wave_system_on_the_largest_tree(orc, dev):  # noqa: F811

@@ -3,7 +3,8 @@
 A step = one classical RK4 step (4 x [ghost fill -> stencils -> right-hand side -> stage update])
 of the 24-field system on the ~1e5-block adaptive tree ("C5"), inputs resident in HBM.
 Prints ONE JSON line: block-point right-hand-side updates per second (fp64, per variable), the
-HBM roofline of the dominant kernel measured live with events on the launch stream, and the CPU
+HBM roofline of the dominant kernel (its launch time measured live with events on the launch stream;
+the counter traffic comes from the committed profile of exactly this build, or is null), and the CPU
 oracle timed on this machine's host cores on a bounded sample of the same workload.
 
 The 24-field system is a throughput workload: with the prescribed step dt = h/4 its second-derivative
@@ -31,18 +32,36 @@ HBM_PEAK_GBS = 8000.0
 STAGE_BYTES = (24.0, 40.0, 40.0, 32.0)
 
 
-def measured_traffic(config, nb):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary
-    (FETCH_SIZE and WRITE_SIZE passes, scaled by the same counters on a device copy of known size),
-    or None when no summary exists for this workload."""
+# fp64 vector peak of the device (256 compute units x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz): prices the arithmetic
+FP64_VECTOR_PEAK_TFLOPS = 78.6
+
+
+def csrc_digest():
+    """SHA-256 over the kernel and host sources of the library (names and contents, sorted): identifies the
+    build that a committed counter summary was taken from."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2007_12792_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        h.update(name.encode())
+        h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()
+
+
+def committed_counters(config, nb):
+    """What the committed rocprofv3 counter summary says about the dominant kernel on this workload: bytes per
+    launch between the L2 caches and the memory fabric (FETCH_SIZE and WRITE_SIZE passes, scaled by the same
+    counters on a device copy of known size) and fp64 operations per launch (SQ_INSTS_VALU_* passes).  The counters
+    cannot be read inside this process, so the record is only used when it was taken from exactly these sources
+    (csrc_sha256) on exactly this tree; otherwise None, and the bench line says traffic: null."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         rec = json.load(open(path)).get(config)
     except (OSError, ValueError):
         return None
-    if not rec or rec.get("n_blocks") != nb:
+    if not rec or rec.get("n_blocks") != nb or rec.get("csrc_sha256") != csrc_digest():
         return None
-    return rec.get("bytes_per_launch")
+    return rec
 
 
 def other_kernels(args, cfg, kind, dev):
@@ -119,12 +138,16 @@ def main():
                     help="instead of the benchmark, time every other kernel of the library once on the workload (the "
                          "literal unzip / rhs_eval / zip calls, the centred ghost rule, the fused right-hand side, the "
                          "regrid transfer) and print one JSON line; this is what the summaries under profiles/ are made with")
+    ap.add_argument("--csrc-digest", action="store_true", help="print the digest of the library sources (the key of profiles/hbm_traffic.json) and exit")
     ap.add_argument("--calibrate-copy", type=float, default=0.0, metavar="GB",
                     help="instead of the benchmark, run 5 plain device copies of this many GB (a kernel of known "
                          "HBM traffic, used to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1")
+    if args.csrc_digest:
+        print(csrc_digest())
+        return
 
     import numpy as np
     import torch
@@ -221,6 +244,12 @@ def main():
     launch_ms = total_ms / (launches_per_step * args.steps)
     bytes_per_launch = sum(stage_bytes) / len(stage_bytes) * nb * 512 * V
     achieved = bytes_per_launch / (launch_ms * 1e-3) / 1e9
+    rec = None if single_rhs else committed_counters(args.config, nb)
+    # roofline time of one launch: the larger of the algorithmic bytes at the HBM peak and the fp64 operations the
+    # counters saw at the vector peak (no counter record for this build: the bytes alone, which dominate)
+    hbm_ms = bytes_per_launch / (HBM_PEAK_GBS * 1e9) * 1e3
+    valu_ms = None if not rec or not rec.get("fp64_flop_per_launch") else rec["fp64_flop_per_launch"] / (FP64_VECTOR_PEAK_TFLOPS * 1e12) * 1e3
+    roofline_ms = max(hbm_ms, valu_ms or 0.0)
     out = {
         "metric": "block-point RHS updates/sec (fp64, per var) + achieved HBM GB/s, 1 GPU",
         "value": value, "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -239,7 +268,12 @@ def main():
                                   ", over the launch schedule" if cfg["kind"] == "SYN24" else "", launches_per_step),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "launch_ms": launch_ms, "algorithmic_bytes_per_launch": bytes_per_launch,
-                     "traffic": None if single_rhs else measured_traffic(args.config, nb),
+                     # bytes between the L2 caches and the memory fabric per launch (HBM plus whatever the memory-side
+                     # cache serves), from the committed counter summary of exactly this build; null otherwise
+                     "traffic": rec["bytes_per_launch"] if rec else None,
+                     "traffic_source": "committed profile (rocprofv3 FETCH_SIZE / WRITE_SIZE, L2 <-> fabric)" if rec else None,
+                     "hbm_ms": hbm_ms, "valu_ms": valu_ms, "roofline_time_ms": roofline_ms,
+                     "roofline_time_frac": roofline_ms / launch_ms,
                      # the same launch time against three byte counts: what the method must move at the very
                      # least (8 B in + 8 B out per update), what this pipeline moves by construction
                      # (= achieved), and what the counters saw (= traffic)
@@ -264,12 +298,13 @@ def main():
         c0 = time.perf_counter()
         ref = to.F(kind, uh, sigma=sg, blocks=blocks)
         cpu_s = time.perf_counter() - c0
-        # also use (every 16th block of) the sample as a live parity check of the kernel just timed
+        # also use the sample as a live parity check of the kernel just timed: every value of every sampled block
         k1 = torch.empty((V, nb, 8, 8, 8), dtype=torch.float64, device=dev)
         tree.rhs_eval_zipped(kind, u0, k1, sigma=sg)
-        got = k1[:, start:start + ns:16].cpu().numpy()
-        want = ref[:, ::16]
-        ok = bool((np.abs(got - want) <= 1e-12 * np.abs(want) + 1e-13).all())
+        ok = True
+        for v in range(V):                               # one field at a time, to bound the temporaries
+            got, want = k1[v, start:start + ns].cpu().numpy(), ref[v]
+            ok = ok and bool((np.abs(got - want) <= 1e-12 * np.abs(want) + 1e-13).all())
         # the same oracle on one thread, on the middle 1/16 of that sample
         import ctypes
         gomp = ctypes.CDLL("libgomp.so.1")
@@ -286,6 +321,8 @@ def main():
                                          "(%d..%d of %d) of the same tree and fields, %.1f s" % (ns, start, start + ns - 1, nb, cpu_s),
                                "parity_on_sample": ok}
     print(json.dumps(out), flush=True)
+    if "cpu_baseline" in out and not out["cpu_baseline"]["parity_on_sample"]:
+        sys.exit("bench.py: the kernel just timed disagrees with the oracle on the sampled blocks")
 
 
 if __name__ == "__main__":

@@ -17,9 +17,14 @@
  *     device.  The caller owns every data array and the workspace.  The library owns only ot_tree
  *     and the device copies of its index tables (released by octree_free).
  *   - device entry points only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
- *     default stream).  They do not synchronise and do not allocate, except that the first device
- *     call on a tree (or octree_upload) copies the index tables to the device, synchronously.
- *     That device must be the current one in every later call on the tree (else OT_E_UNSUPPORTED).
+ *     default stream).  They do not synchronise and do not allocate, with one exception: the device
+ *     copies of a tree's index tables are a cache inside the opaque handle, which the first device
+ *     call on the tree fills (one hipMalloc and synchronous copies; this fails inside a stream
+ *     capture).  Call octree_upload beforehand where that matters: after it no device call on the
+ *     tree allocates or synchronises.  The device that was current then must be the current one in
+ *     every later call on the tree (else OT_E_UNSUPPORTED).
+ *   - data arrays hold doubles and must be 8-byte aligned, workspaces 256-byte aligned
+ *     (OT_E_BADARG otherwise).
  *   - calls that use the same tree, plan or workspace must not overlap in time.
  *   - layouts (x fastest): zipped  [var][block][k][j][i]     8*8*8   doubles per block and variable
  *                          padded  [var][block][kk][jj][ii]  14*14*14, (ii,jj,kk) = (i,j,k)+3
@@ -60,7 +65,7 @@ typedef struct {
     uint32_t lmin, lmax;         /* 3 <= lmin <= lmax <= 19                                        */
     uint32_t npts;               /* number of seed points                                          */
     const uint32_t *pts_q20;     /* host, 3*npts coordinates on the 2^20 lattice                   */
-    const uint32_t *radius_q20;  /* host, lmax-lmin radii R_l for l = lmin .. lmax-1 (same lattice) */
+    const uint32_t *radius_q20;  /* host, lmax-lmin radii R_l <= 2^21 for l = lmin .. lmax-1 (same lattice) */
     uint32_t points_per_dim;     /* must be 8                                                      */
     uint32_t pad;                /* must be 3                                                      */
     uint32_t periodic;           /* must be 1                                                      */
@@ -109,7 +114,7 @@ int ot_rhs_nvar_out(ot_rhs_kind kind);
  * f = P - 16a' in [0,16): node f/2 if f is even, else 6-point Lagrange interpolation on that
  * leaf's own nodes s..s+5, s = clamp((f-1)/2 - 2, 0, 2).  Axes are interpolated in the order
  * x, y, z, each as acc = w0*v0, acc = fma(w_m, v_m, acc). */
-int unzip(ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev, void *hip_stream);
+int unzip(const ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev, void *hip_stream);
 
 /* rhs_eval: padded_dev [nvar_in][nb][14^3] -> rhs_padded_dev [nvar_out][nb][14^3]; only the 8^3
  * interior of each output block is written.  Sixth-order centred first and second derivatives,
@@ -131,27 +136,32 @@ int unzip(ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev,
  *   D1 = (fma(45,d1, fma(-9,d2, d3)) * (1/60)) / h;
  *   D2 = (fma(-490,u0, fma(270,s1, fma(-27,s2, 2*s3))) * (1/180)) / h^2;  Laplacian = (D2x+D2y)+D2z;
  *   KO = sigma * (((q_x+q_y)+q_z) / (64 h)),  q = fma(-20,u0, fma(15,s1, fma(-6,s2, s3))). */
-int rhs_eval(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
+int rhs_eval(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
              const double *padded_dev, double *rhs_padded_dev, void *hip_stream);
 
 /* zip: padded_dev [nvar][nb][14^3] -> zipped_dev [nvar][nb][8^3]; drops the ghost layers.
  * OT_E_UNSUPPORTED when nb * nvar exceeds 2^31 - 1 (one workgroup per block and variable). */
-int zip(ot_tree *tree, int nvar, const double *padded_dev, double *zipped_dev, void *hip_stream);
+int zip(const ot_tree *tree, int nvar, const double *padded_dev, double *zipped_dev, void *hip_stream);
 
 /* The three calls above fused: zipped in, zipped right-hand side out, no padded array in memory.
  * Bit-identical to zip(rhs_eval(unzip(.))).  For SYN24 both rhs_eval and rhs_eval_zipped use
  * variables 10..19 of the output array as scratch while they run (each is overwritten with its
  * final value before the call's work completes). */
-int rhs_eval_zipped(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
+int rhs_eval_zipped(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
                     const double *zipped_dev, double *rhs_zipped_dev, void *hip_stream);
 
 /* Classical fourth-order Runge-Kutta step of d_t u = F(u), F = zip(rhs_eval(unzip(.))):
  *   k1 = F(u), k2 = F(u + dt/2 k1), k3 = F(u + dt/2 k2), k4 = F(u + dt k3),
  *   u <- u + dt/6 (((k1 + 2 k2) + 2 k3) + k4),  every a*k + u evaluated as one fma.
  * u_zipped_dev [nvar][nb][8^3] is updated in place.  workspace_dev must hold at least
- * rk_workspace_bytes() bytes (three zipped state vectors) and be 256-byte aligned. */
+ * rk_workspace_bytes() bytes (three zipped state vectors), be 256-byte aligned and not overlap u
+ * (OT_E_BADARG otherwise).
+ * Ghost values at level jumps follow unzip's rule, whose outermost row extrapolates by half a
+ * coarse cell.  That row makes level jumps unstable for wave propagation over many steps (the wave
+ * system on a three-level tree, sigma = 0.4: max |u| grows past 1e9 by t = 1); for evolutions
+ * use rk_step_centred below, which is stable there. */
 int rk_workspace_bytes(const ot_tree *tree, ot_rhs_kind kind, size_t *bytes);
-int rk_step(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,
+int rk_step(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,
             double *u_zipped_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 /* Variant of the ghost rule with centred interpolation stencils (level-ordered).  Identical to
@@ -169,9 +179,9 @@ int rk_step(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double
  * written to memory (level by level, before each stage); everything else is fused as in rk_step.
  * Its workspace holds three zipped state vectors followed by those padded blocks
  * (rk_centred_workspace_bytes), 256-byte aligned. */
-int unzip_centred(ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev, void *hip_stream);
+int unzip_centred(const ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev, void *hip_stream);
 int rk_centred_workspace_bytes(const ot_tree *tree, ot_rhs_kind kind, size_t *bytes);
-int rk_step_centred(ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,
+int rk_step_centred(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,
                     double *u_zipped_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 /* Regrid: the tree that follows the moved refinement centres is built with octree_build; a

@@ -250,6 +250,8 @@ static int64_t balance(orc_tree *t)
 int64_t orc_tree_build(int lmin, int lmax, int npts, const uint32_t *pts, const uint32_t *radius, void **out)
 {
     if (lmin < 3 || lmax < lmin || lmax > MAXLEVEL || npts < 0 || !out) return -1;
+    for (int l = lmin; l < lmax; l++)                     /* radii beyond twice the cube's edge: rejected (R*R stays far from 2^63) */
+        if (radius[l - lmin] > (2u << QBITS)) return -1;
     orc_tree *t = tree_new();
     uint32_t n0 = 1u << lmin;
     for (uint32_t z = 0; z < n0; z++) for (uint32_t y = 0; y < n0; y++) for (uint32_t x = 0; x < n0; x++)

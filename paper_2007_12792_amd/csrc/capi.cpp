@@ -12,16 +12,18 @@
 
 using namespace octfd;
 
+// The device copies of the tables are a cache inside the opaque handle: the device entry points take the tree
+// as const and fill the cache on first use (octree_upload fills it ahead of time).
 struct ot_tree {
     HostTree host;
-    ot_leaf* d_leaves = nullptr;
-    int32_t* d_ghost = nullptr;
-    int32_t* d_coarse = nullptr;
-    int32_t* d_by_level = nullptr;
-    int32_t* d_src_slot = nullptr;
-    int32_t* d_src_by_level = nullptr;
-    int32_t* d_sched = nullptr;
-    int device = -1;   // device the tables live on, -1 = not uploaded
+    mutable ot_leaf* d_leaves = nullptr;
+    mutable int32_t* d_ghost = nullptr;
+    mutable int32_t* d_coarse = nullptr;
+    mutable int32_t* d_by_level = nullptr;
+    mutable int32_t* d_src_slot = nullptr;
+    mutable int32_t* d_src_by_level = nullptr;
+    mutable int32_t* d_sched = nullptr;
+    mutable int device = -1;   // device the tables live on, -1 = not uploaded
 };
 
 struct ot_transfer {
@@ -52,7 +54,7 @@ int same_device(int device)
     return cur == device ? OT_OK : OT_E_UNSUPPORTED;
 }
 
-int ensure_device(ot_tree* t)
+int ensure_device(const ot_tree* t)
 {
     if (t->device >= 0) return same_device(t->device);
     // kernels address one variable's zipped array with 32-bit byte offsets
@@ -133,6 +135,9 @@ DeviceTree dev_view(const ot_tree* t)
 }
 
 bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }
+
+// data arrays hold doubles: anything else cannot be a valid array and would fault in the kernels
+bool aligned8(const void* p) { return reinterpret_cast<uintptr_t>(p) % 8 == 0; }
 
 }  // namespace
 
@@ -226,46 +231,48 @@ int ot_rhs_nvar_out(ot_rhs_kind kind)
     }
 }
 
-int unzip(ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
+int unzip(const ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
 {
-    if (!tree || nvar <= 0 || !zipped_dev || !padded_dev) return OT_E_BADARG;
+    if (!tree || nvar <= 0 || !zipped_dev || !padded_dev || !aligned8(zipped_dev) || !aligned8(padded_dev)) return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;   // < 2^20 blocks, and the grid is at most 8 workgroups per block
     hipError_t e = launch_unzip(dev_view(tree), nvar, zipped_dev, padded_dev, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
-int unzip_centred(ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
+int unzip_centred(const ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
 {
-    if (!tree || nvar <= 0 || !zipped_dev || !padded_dev) return OT_E_BADARG;
+    if (!tree || nvar <= 0 || !zipped_dev || !padded_dev || !aligned8(zipped_dev) || !aligned8(padded_dev)) return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
     hipError_t e = launch_unzip_centred(dev_view(tree), tree->host.level_start, false, nvar, zipped_dev, padded_dev,
                                         static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
-int zip(ot_tree* tree, int nvar, const double* padded_dev, double* zipped_dev, void* hip_stream)
+int zip(const ot_tree* tree, int nvar, const double* padded_dev, double* zipped_dev, void* hip_stream)
 {
-    if (!tree || nvar <= 0 || !zipped_dev || !padded_dev) return OT_E_BADARG;
+    if (!tree || nvar <= 0 || !zipped_dev || !padded_dev || !aligned8(zipped_dev) || !aligned8(padded_dev)) return OT_E_BADARG;
     if (tree->host.leaves.size() * static_cast<size_t>(nvar) > 0x7fffffffu) return OT_E_UNSUPPORTED;   // one workgroup each
     if (int rc = ensure_device(tree)) return rc;
     hipError_t e = launch_zip(dev_view(tree), nvar, padded_dev, zipped_dev, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
-int rhs_eval(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, const double* padded_dev,
+int rhs_eval(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, const double* padded_dev,
              double* rhs_padded_dev, void* hip_stream)
 {
-    if (!tree || !kind_ok(kind) || !params || !padded_dev || !rhs_padded_dev) return OT_E_BADARG;
+    if (!tree || !kind_ok(kind) || !params || !padded_dev || !rhs_padded_dev || !aligned8(padded_dev) || !aligned8(rhs_padded_dev))
+        return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
     RhsArgs a{padded_dev, rhs_padded_dev, nullptr, nullptr, nullptr, rhs_padded_dev, 0.0, params->ko_sigma};
     hipError_t e = launch_rhs(dev_view(tree), kind, false, false, kOutPadded, a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
-int rhs_eval_zipped(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, const double* zipped_dev,
+int rhs_eval_zipped(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, const double* zipped_dev,
                     double* rhs_zipped_dev, void* hip_stream)
 {
-    if (!tree || !kind_ok(kind) || !params || !zipped_dev || !rhs_zipped_dev) return OT_E_BADARG;
+    if (!tree || !kind_ok(kind) || !params || !zipped_dev || !rhs_zipped_dev || !aligned8(zipped_dev) || !aligned8(rhs_zipped_dev))
+        return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
     RhsArgs a{zipped_dev, rhs_zipped_dev, nullptr, nullptr, nullptr, rhs_zipped_dev, 0.0, params->ko_sigma};
     hipError_t e = launch_rhs(dev_view(tree), kind, true, false, kOutZipped, a, static_cast<hipStream_t>(hip_stream));
@@ -280,22 +287,26 @@ int rk_workspace_bytes(const ot_tree* tree, ot_rhs_kind kind, size_t* bytes)
     return OT_OK;
 }
 
-int rk_step(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u_zipped_dev,
-            void* workspace_dev, size_t workspace_bytes, void* hip_stream)
+// checks shared by the stepping calls: u holds doubles, the workspace is large enough and 256-byte aligned, and the
+// two do not overlap (the stage kernels read ghosts of u while they write stage vectors into the workspace)
+static int check_step_buffers(const double* u, size_t u_bytes, const void* ws, size_t ws_bytes, size_t need)
 {
-    if (!tree || !kind_ok(kind) || !params || !u_zipped_dev || !workspace_dev) return OT_E_BADARG;
-    size_t need = 0;
-    if (int rc = rk_workspace_bytes(tree, kind, &need)) return rc;
-    if (workspace_bytes < need) return OT_E_WORKSPACE;
-    if (reinterpret_cast<uintptr_t>(workspace_dev) % 256) return OT_E_BADARG;
-    if (int rc = ensure_device(tree)) return rc;
+    if (ws_bytes < need) return OT_E_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(ws) % 256 || !aligned8(u)) return OT_E_BADARG;
+    const uintptr_t u0 = reinterpret_cast<uintptr_t>(u), w0 = reinterpret_cast<uintptr_t>(ws);
+    if (u0 < w0 + need && w0 < u0 + u_bytes) return OT_E_BADARG;
+    return OT_OK;
+}
+
+// the four stage launches of rk_step on tables that are already on the device
+static int rk_step_launch(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u,
+                          void* workspace_dev, size_t need, hipStream_t s)
+{
     const size_t len = need / (3 * sizeof(double));
     double* acc = static_cast<double*>(workspace_dev);
     double* sa = acc + len;
     double* sb = sa + len;
-    double* u = u_zipped_dev;
     const DeviceTree dv = dev_view(tree);
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const double sg = params->ko_sigma;
     // stage vectors ping-pong between sa and sb: a stage reads ghosts of the vector it was given
     // while writing the next one, so the two must be different arrays
@@ -312,6 +323,17 @@ int rk_step(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double
     return OT_OK;
 }
 
+int rk_step(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u_zipped_dev,
+            void* workspace_dev, size_t workspace_bytes, void* hip_stream)
+{
+    if (!tree || !kind_ok(kind) || !params || !u_zipped_dev || !workspace_dev) return OT_E_BADARG;
+    size_t need = 0;
+    if (int rc = rk_workspace_bytes(tree, kind, &need)) return rc;
+    if (int rc = check_step_buffers(u_zipped_dev, need / 3, workspace_dev, workspace_bytes, need)) return rc;
+    if (int rc = ensure_device(tree)) return rc;
+    return rk_step_launch(tree, kind, params, dt, u_zipped_dev, workspace_dev, need, static_cast<hipStream_t>(hip_stream));
+}
+
 int rk_centred_workspace_bytes(const ot_tree* tree, ot_rhs_kind kind, size_t* bytes)
 {
     size_t zipped3 = 0;
@@ -321,15 +343,14 @@ int rk_centred_workspace_bytes(const ot_tree* tree, ot_rhs_kind kind, size_t* by
     return OT_OK;
 }
 
-int rk_step_centred(ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u_zipped_dev,
+int rk_step_centred(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u_zipped_dev,
                     void* workspace_dev, size_t workspace_bytes, void* hip_stream)
 {
     if (!tree || !kind_ok(kind) || !params || !u_zipped_dev || !workspace_dev) return OT_E_BADARG;
     size_t need = 0, zipped3 = 0;
     if (int rc = rk_centred_workspace_bytes(tree, kind, &need)) return rc;
     if (int rc = rk_workspace_bytes(tree, kind, &zipped3)) return rc;
-    if (workspace_bytes < need) return OT_E_WORKSPACE;
-    if (reinterpret_cast<uintptr_t>(workspace_dev) % 256) return OT_E_BADARG;
+    if (int rc = check_step_buffers(u_zipped_dev, zipped3 / 3, workspace_dev, workspace_bytes, need)) return rc;
     if (int rc = ensure_device(tree)) return rc;
     const size_t len = zipped3 / (3 * sizeof(double));
     const int nvar = ot_rhs_nvar_in(kind);

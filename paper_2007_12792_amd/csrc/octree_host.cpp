@@ -286,6 +286,10 @@ int build_tree(const ot_build_params& p, HostTree& out)
     if (p.lmax > p.lmin && !p.radius_q20) return OT_E_BADARG;
     for (uint32_t q = 0; q < 3 * p.npts; ++q)
         if (p.pts_q20[q] >> kQBits) return OT_E_BADARG;
+    // no two points of the periodic cube are further apart than sqrt(3) * 2^19 lattice units; larger radii say
+    // nothing more, and beyond 2^31.5 their square would overflow the 64-bit comparison in near_seed()
+    for (uint32_t l = p.lmin; l < p.lmax; ++l)
+        if (p.radius_q20[l - p.lmin] > (2u << kQBits)) return OT_E_BADARG;
 
     Octree t;
     std::deque<int32_t> work{0};

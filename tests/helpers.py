@@ -1,5 +1,34 @@
-"""Shared test helpers: node coordinates and small trees (no method arithmetic)."""
+"""Shared test helpers: node coordinates, small trees and the comparison against the oracle (no method arithmetic)."""
 import numpy as np
+
+KIND = {"DERIVS": 0, "WAVE": 1, "BURGERS": 2, "SYN24": 3}
+# fp64 values: pass iff |gpu - oracle| <= RTOL |oracle| + ATOL
+RTOL, ATOL = 1e-12, 1e-13
+
+
+def assert_close(got, want, what):
+    got, want = np.asarray(got), np.asarray(want)
+    assert got.shape == want.shape
+    assert np.isfinite(want).all() and np.isfinite(got).all(), what
+    err = np.abs(got - want)
+    bound = RTOL * np.abs(want) + ATOL
+    nz = int((got != want).sum())
+    print("%s: %d of %d values differ, worst |diff|/bound = %.3g" % (what, nz, got.size, (err / bound).max()), flush=True)
+    assert (err <= bound).all(), what
+
+
+def dev_empty(shape, dev):
+    """NaN-filled device array, so that a point the kernel failed to write cannot pass by accident"""
+    import torch
+    return torch.full(shape, float("nan"), dtype=torch.float64, device=dev)
+
+
+def trees(orc, name, seed=1):
+    """the oracle's and the library's tree of a named workload"""
+    import paper_2007_12792_amd as octfd
+    import synthdata as sd
+    p = sd.tree_params(name, seed)
+    return orc.Tree.build(**p), octfd.Tree.build(**p)
 
 
 def coords(leaves):

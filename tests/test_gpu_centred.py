@@ -8,27 +8,9 @@ import torch
 
 import paper_2007_12792_amd as octfd
 import synthdata as sd
+from helpers import KIND, assert_close
 
 pytestmark = pytest.mark.gpu
-KIND = {"DERIVS": 0, "WAVE": 1, "BURGERS": 2, "SYN24": 3}
-RTOL, ATOL = 1e-12, 1e-13
-
-
-@pytest.fixture(scope="module")
-def dev():
-    if not torch.cuda.is_available():
-        pytest.skip("needs a GPU")
-    return torch.device("cuda:0")
-
-
-def assert_close(got, want, what):
-    got, want = np.asarray(got), np.asarray(want)
-    assert got.shape == want.shape
-    assert np.isfinite(want).all() and np.isfinite(got).all(), what
-    err = np.abs(got - want)
-    bound = RTOL * np.abs(want) + ATOL
-    print("%s: %d of %d values differ, worst |diff|/bound = %.3g" % (what, int((got != want).sum()), got.size, (err / bound).max()), flush=True)
-    assert (err <= bound).all(), what
 
 
 def nan_like(shape, dev):

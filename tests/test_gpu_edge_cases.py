@@ -7,7 +7,7 @@ import torch
 
 import paper_2007_12792_amd as octfd
 import synthdata as sd
-from test_gpu_parity import assert_close, dev, dev_empty, trees  # noqa: F401
+from helpers import assert_close, dev_empty, trees
 
 pytestmark = pytest.mark.gpu
 TP = 2.0 * np.pi
@@ -19,7 +19,7 @@ def uniform(orc, level):
 
 
 @pytest.mark.parametrize("kind", [0, 1, 2, 3])
-def test_uniform_level3_every_kind(orc, dev, kind):  # noqa: F811
+def test_uniform_level3_every_kind(orc, dev, kind):
     to, tg = uniform(orc, 3)
     rng = np.random.default_rng(30 + kind)
     u = rng.standard_normal((octfd.nvar_in(kind), to.n, 8, 8, 8))
@@ -30,7 +30,7 @@ def test_uniform_level3_every_kind(orc, dev, kind):  # noqa: F811
 
 
 @pytest.mark.parametrize("seed", [2, 3])
-def test_other_seeds_syn24_rk_step(orc, dev, seed):  # noqa: F811
+def test_other_seeds_syn24_rk_step(orc, dev, seed):
     to, tg = trees(orc, "T4", seed)
     u = sd.make_fields("T4", to.leaves, seed).numpy()
     dt = sd.time_step(5)
@@ -41,7 +41,7 @@ def test_other_seeds_syn24_rk_step(orc, dev, seed):  # noqa: F811
     assert_close(ud.cpu().numpy(), want, "T4 seed %d" % seed)
 
 
-def test_block_with_seven_coarser_sources(orc, dev):  # noqa: F811
+def test_block_with_seven_coarser_sources(orc, dev):
     # one level-3 octant refined twice around a single point: the level-5 blocks in the corners of
     # the level-4 octet see coarser leaves on three faces, three edges and one corner
     p = dict(lmin=3, lmax=5, pts_q20=np.array([[530000, 530000, 530000]], np.uint32), radius_q20=np.array([20000, 3000], np.uint32))
@@ -60,7 +60,7 @@ def test_block_with_seven_coarser_sources(orc, dev):  # noqa: F811
     assert_close(out.cpu().numpy(), to.F(3, u, sigma=0.4), "seven coarser sources")
 
 
-def test_invariants_hold_bit_for_bit(orc, dev):  # noqa: F811
+def test_invariants_hold_bit_for_bit(orc, dev):
     to, tg = trees(orc, "T3")
     rng = np.random.default_rng(41)
     u = torch.from_numpy(rng.standard_normal((2, to.n, 8, 8, 8))).to(dev)
@@ -83,7 +83,7 @@ def test_invariants_hold_bit_for_bit(orc, dev):  # noqa: F811
     assert torch.equal(back, u)                           # zip(unzip(u)) == u
 
 
-def test_burgers_many_steps_towards_the_shock(orc, dev):  # noqa: F811
+def test_burgers_many_steps_towards_the_shock(orc, dev):
     # the paper's equation and initial data with c = 1 on a uniform 128^3 lattice, integrated to
     # t = 0.15 (the shock forms at 1/pi = 0.318): compare with the solution by characteristics
     to, tg = uniform(orc, 4)
@@ -121,7 +121,7 @@ def corner_params(lmax=6):
     return dict(lmin=3, lmax=lmax, pts_q20=pts, radius_q20=np.array([90000, 60000, 40000][:lmax - 3], np.uint32))
 
 
-def test_level_jumps_across_the_periodic_wrap(orc, dev):  # noqa: F811
+def test_level_jumps_across_the_periodic_wrap(orc, dev):
     p = corner_params()
     to, tg = orc.Tree.build(**p), octfd.Tree.build(**p)
     assert (to.leaves == tg.leaves).all() and (to.ghost_table() == tg.ghost_table()).all()
@@ -159,7 +159,7 @@ def test_level_jumps_across_the_periodic_wrap(orc, dev):  # noqa: F811
     assert_close(got.cpu().numpy(), orc.transfer(to, to2, u[:2]), "regrid across the wrap")
 
 
-def test_thirteen_levels(orc, dev):  # noqa: F811
+def test_thirteen_levels(orc, dev):
     """levels 3..15 around one point: grid spacings from 2^-6 down to 2^-18 in one tree"""
     lmax = 15
     rad = np.array([int(1.6 * 2 ** (20 - l)) for l in range(3, lmax)], np.uint32)
@@ -186,7 +186,7 @@ def test_thirteen_levels(orc, dev):  # noqa: F811
 
 
 @pytest.mark.parametrize("name,kind,nsteps", [("T3", 1, 3), ("T4", 3, 2)])
-def test_rk_step_can_be_captured_in_a_graph_and_replayed(dev, name, kind, nsteps):  # noqa: F811
+def test_rk_step_can_be_captured_in_a_graph_and_replayed(dev, name, kind, nsteps):
     """After octree_upload the device calls only enqueue kernels: no allocation, no synchronisation,
     no memset.  A step captured in a graph must replay to the same bits as eager steps, every time.
     (Two steps only for the 24-field system, whose values overflow after a few steps at this dt.)"""
@@ -221,7 +221,7 @@ def test_rk_step_can_be_captured_in_a_graph_and_replayed(dev, name, kind, nsteps
         assert np.isfinite((eager[n] * 0.5).sum().item())   # eager work and a synchronisation between replays
 
 
-def test_two_trees_step_concurrently_on_two_streams(dev):  # noqa: F811
+def test_two_trees_step_concurrently_on_two_streams(dev):
     # calls on different trees may overlap: steps of a wave tree and of a 24-field tree issued alternately on two
     # streams give the bits of the same steps issued one after the other
     ta, tb = octfd.Tree.build(**sd.tree_params("T3")), octfd.Tree.build(**sd.tree_params("T4"))
@@ -251,7 +251,7 @@ def test_two_trees_step_concurrently_on_two_streams(dev):  # noqa: F811
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13, 14, 15, 16])
-def test_random_trees_24_field_right_hand_side(orc, dev, seed):  # noqa: F811
+def test_random_trees_24_field_right_hand_side(orc, dev, seed):
     # random refinement centres, radii and depths: many shapes of level jumps (one to seven coarser sources per
     # block, corner-only sources, units of the launch schedule that are mostly padding), every value compared
     rng = np.random.default_rng(seed)

@@ -10,39 +10,9 @@ import torch
 
 import paper_2007_12792_amd as octfd
 import synthdata as sd
+from helpers import KIND, assert_close, dev_empty, trees
 
 pytestmark = pytest.mark.gpu
-
-KIND = {"DERIVS": 0, "WAVE": 1, "BURGERS": 2, "SYN24": 3}
-RTOL, ATOL = 1e-12, 1e-13
-
-
-@pytest.fixture(scope="module")
-def dev():
-    if not torch.cuda.is_available():
-        pytest.skip("needs a GPU")
-    return torch.device("cuda:0")
-
-
-def assert_close(got, want, what):
-    got, want = np.asarray(got), np.asarray(want)
-    assert got.shape == want.shape
-    assert np.isfinite(want).all() and np.isfinite(got).all(), what
-    err = np.abs(got - want)
-    bound = RTOL * np.abs(want) + ATOL
-    nz = int((got != want).sum())
-    print("%s: %d of %d values differ, worst |diff|/bound = %.3g" % (what, nz, got.size, (err / bound).max()), flush=True)
-    assert (err <= bound).all(), what
-
-
-def trees(orc, name, seed=1):
-    p = sd.tree_params(name, seed)
-    return orc.Tree.build(**p), octfd.Tree.build(**p)
-
-
-def dev_empty(shape, dev):
-    # NaN-filled so that a point the kernel failed to write cannot pass by accident
-    return torch.full(shape, float("nan"), dtype=torch.float64, device=dev)
 
 
 @pytest.mark.parametrize("name,nvar", [("C1", 1), ("T2", 1), ("T4", 3), ("T4", 8), ("T2", 13)])
@@ -152,16 +122,18 @@ def test_config2_full_parity(orc, dev):
     assert_close(fd.cpu().numpy(), want, "C2 DERIVS")
 
 
-def test_config4_sampled_parity(orc, dev):
+def test_config4_full_parity(orc, dev):
+    # the 21,064-block tree, 24 fields: every value of the fused right-hand side and of one whole step
     to, tg = trees(orc, "C4")
     ud = sd.make_fields("C4", to.leaves, device=dev)
     u = ud.cpu().numpy()
     fd = dev_empty((24, to.n, 8, 8, 8), dev)
-    tg.rhs_eval_zipped(3, ud, fd, sigma=0.4)
-    lev = to.leaves[:, 0]
-    sample = np.unique(np.concatenate([np.arange(0, to.n, 41), np.flatnonzero(lev < lev.max())[::5]]))
-    want = to.F(3, u, sigma=0.4, blocks=sample)
-    assert_close(fd[:, torch.from_numpy(sample).to(dev)].cpu().numpy(), want, "C4 SYN24 sampled")
+    tg.rhs_eval_zipped(3, ud, fd, sigma=sd.KO_SIGMA)
+    assert_close(fd.cpu().numpy(), to.F(3, u, sigma=sd.KO_SIGMA), "C4 SYN24 rhs_eval_zipped, every block")
+    dt = sd.time_step(7)
+    ws = torch.empty(tg.rk_workspace_bytes(3) // 8, dtype=torch.float64, device=dev)
+    tg.rk_step(3, ud, dt, ws, sigma=sd.KO_SIGMA)
+    assert_close(ud.cpu().numpy(), to.rk4_step(3, u, dt, sigma=sd.KO_SIGMA), "C4 SYN24 rk_step, every value")
 
 
 @pytest.mark.parametrize("name", ["C3", "C3B"])

@@ -8,16 +8,9 @@ import torch
 
 import paper_2007_12792_amd as octfd
 import synthdata as sd
+from helpers import ATOL, RTOL
 
 pytestmark = pytest.mark.gpu
-RTOL, ATOL = 1e-12, 1e-13
-
-
-@pytest.fixture(scope="module")
-def dev():
-    if not torch.cuda.is_available():
-        pytest.skip("needs a GPU")
-    return torch.device("cuda:0")
 
 
 def both(orc, params):

@@ -122,6 +122,30 @@ def test_bad_arguments_are_reported_not_crashed():
     rp = octfd.RhsParams(0.4)
     assert L.rk_step(t._h, octfd.WAVE, C.byref(rp), 0.1, one, one, 16, None) == octfd.OT_E_WORKSPACE
     assert octfd.strerror(octfd.OT_E_WORKSPACE) == "workspace too small"
+    # buffers of the stepping calls (checked before any device work): alignment, and u apart from the workspace
+    need = t.rk_workspace_bytes(octfd.WAVE)
+    u, ws = C.c_void_p(1 << 30), C.c_void_p(1 << 32)
+    for fn in (L.rk_step, L.rk_step_centred):
+        assert fn(t._h, octfd.WAVE, C.byref(rp), 0.1, C.c_void_p((1 << 30) + 4), ws, need, None) == octfd.OT_E_BADARG    # u not 8-byte aligned
+        assert fn(t._h, octfd.WAVE, C.byref(rp), 0.1, u, C.c_void_p((1 << 32) + 128), need, None) == octfd.OT_E_BADARG   # workspace not 256-byte aligned
+        assert fn(t._h, octfd.WAVE, C.byref(rp), 0.1, C.c_void_p((1 << 32) + need - 256), ws, need, None) == octfd.OT_E_BADARG   # u begins inside the workspace
+        assert fn(t._h, octfd.WAVE, C.byref(rp), 0.1, C.c_void_p((1 << 32) - 256), ws, need, None) == octfd.OT_E_BADARG          # u ends inside it
+    assert L.unzip(t._h, 1, C.c_void_p(4100), C.c_void_p(8192), None) == octfd.OT_E_BADARG
+
+
+def test_radii_beyond_the_cube_are_refused(orc):
+    # R > 2^21 lattice units (twice the cube's edge) is refused by the library and by the oracle alike; 2^21 itself
+    # refines everything, like any radius beyond the cube's diagonal
+    pts = np.array([[5, 6, 7]], np.uint32)
+    with pytest.raises(octfd.OctfdError) as e:
+        octfd.Tree.build(3, 4, pts, np.array([(1 << 21) + 1], np.uint32))
+    assert e.value.status == octfd.OT_E_BADARG
+    with pytest.raises(ValueError):
+        orc.Tree.build(3, 4, pts, np.array([(1 << 21) + 1], np.uint32))
+    with pytest.raises(octfd.OctfdError):
+        octfd.Tree.build(3, 4, pts, np.array([0xffffffff], np.uint32))
+    a, b = octfd.Tree.build(3, 4, pts, np.array([1 << 21], np.uint32)), orc.Tree.build(3, 4, pts, np.array([1 << 21], np.uint32))
+    assert a.n == 4096 and (a.leaves == b.leaves).all()
 
 
 def test_device_calls_report_missing_gpu_without_crashing():

@@ -98,7 +98,8 @@ int octree_get_leaves(const ot_tree *tree, ot_leaf *out, size_t cap);
  * (finer: 4 ids across a face, 2 along an edge, 1 at a corner).  Entry d = 13 is the block itself. */
 int octree_get_ghost_table(const ot_tree *tree, int32_t *out, size_t cap);
 
-/* Copies the index tables to the current device now (otherwise done by the first device call). */
+/* Copies the index tables to the current device now (otherwise done by the first device call), and
+ * resolves the address of the library's static scratch array on that device (see rk_step_static). */
 int octree_upload(ot_tree *tree);
 
 int octree_free(ot_tree *tree); /* NULL is allowed */
@@ -163,6 +164,20 @@ int rhs_eval_zipped(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *
 int rk_workspace_bytes(const ot_tree *tree, ot_rhs_kind kind, size_t *bytes);
 int rk_step(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,
             double *u_zipped_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): rk_step with its workspace in a static device array of
+ * OT_STATIC_WORKSPACE_BYTES that the library's code object holds on every GPU it is loaded on,
+ * until the process ends.  Same arithmetic and results as rk_step.  The call allocates nothing and
+ * does not synchronise; octree_upload(tree) must have been called on the current device before
+ * (OT_E_UNSUPPORTED otherwise), and rk_workspace_bytes(tree, kind) must not exceed
+ * OT_STATIC_WORKSPACE_BYTES (OT_E_WORKSPACE otherwise; e.g. the wave system on up to 3,400 blocks).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU race, even
+ * on different trees or streams.  Nothing in the array needs clearing between calls (every word
+ * a step reads it has written before). */
+#define OT_STATIC_WORKSPACE_BYTES ((size_t)160 << 20)
+int rk_step_static(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,
+                   double *u_zipped_dev, void *hip_stream);
 
 /* Variant of the ghost rule with centred interpolation stencils (level-ordered).  Identical to
  * unzip except for padded points whose containing leaf L is one level coarser: there every odd

@@ -16,10 +16,11 @@ DERIVS, WAVE, BURGERS, SYN24 = 0, 1, 2, 3
 KINDS = {"DERIVS": DERIVS, "WAVE": WAVE, "BURGERS": BURGERS, "SYN24": SYN24}
 OT_OK, OT_E_BADARG, OT_E_NOMEM, OT_E_UNBALANCED, OT_E_INCOMPLETE = 0, -1, -2, -3, -4
 OT_E_WORKSPACE, OT_E_HIP, OT_E_NODEVICE, OT_E_UNSUPPORTED = -5, -6, -7, -8
+STATIC_WORKSPACE_BYTES = 160 << 20   # OT_STATIC_WORKSPACE_BYTES
 
 EXPORTS = ["octree_build", "octree_from_leaves", "octree_num_blocks", "octree_get_leaves",
            "octree_get_ghost_table", "octree_upload", "octree_free", "ot_rhs_nvar_in", "ot_rhs_nvar_out",
-           "unzip", "rhs_eval", "zip", "rhs_eval_zipped", "rk_workspace_bytes", "rk_step",
+           "unzip", "rhs_eval", "zip", "rhs_eval_zipped", "rk_workspace_bytes", "rk_step", "rk_step_static",
            "unzip_centred", "rk_centred_workspace_bytes", "rk_step_centred",
            "regrid_plan", "regrid_table", "regrid_transfer", "regrid_free",
            "ot_strerror", "ot_last_hip_error"]
@@ -70,6 +71,7 @@ def lib():
         "rhs_eval_zipped": [vp, i32, C.POINTER(RhsParams), vp, vp, vp],
         "rk_workspace_bytes": [vp, i32, C.POINTER(sz)],
         "rk_step": [vp, i32, C.POINTER(RhsParams), dbl, vp, vp, sz, vp],
+        "rk_step_static": [vp, i32, C.POINTER(RhsParams), dbl, vp, vp],
         "unzip_centred": [vp, i32, vp, vp, vp],
         "rk_centred_workspace_bytes": [vp, i32, C.POINTER(sz)],
         "rk_step_centred": [vp, i32, C.POINTER(RhsParams), dbl, vp, vp, sz, vp],
@@ -223,6 +225,12 @@ class Tree:
         nbytes = workspace.numel() * workspace.element_size()
         _check(lib().rk_step(self._h, kind, C.byref(p), float(dt), _ptr(u), _ptr(workspace), nbytes, _stream(stream)),
                "rk_step")
+
+    def rk_step_static(self, kind, u, dt, sigma=0.0, stream=None):
+        """rk_step with the library's static device workspace (allocates nothing; needs upload() first)"""
+        _shape(u, (nvar_in(kind), self.n, 8, 8, 8), "u")
+        p = RhsParams(float(sigma))
+        _check(lib().rk_step_static(self._h, kind, C.byref(p), float(dt), _ptr(u), _stream(stream)), "rk_step_static")
 
     def rk_centred_workspace_bytes(self, kind):
         n = C.c_size_t()

@@ -33,9 +33,31 @@ struct ot_transfer {
     int device = -1;
 };
 
+// Workspace of rk_step_static: one copy per GPU, held by the code object until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress; kernels receive the resolved address (g_static_ws).
+static __device__ __align__(256) unsigned char scratch[OT_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 std::atomic<int> g_last_hip{0};
+
+int hip_fail(hipError_t e);
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_static_ws[kMaxDevices];   // per device: address of `scratch` there, null until resolved
+
+// once per device, with that device current (called from the upload of a tree's tables)
+int resolve_static_workspace(int dev)
+{
+    if (dev < 0 || dev >= kMaxDevices) return OT_E_UNSUPPORTED;
+    if (g_static_ws[dev].load()) return OT_OK;
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (!ptr || reinterpret_cast<uintptr_t>(ptr) % 256) return OT_E_HIP;
+    g_static_ws[dev].store(ptr);
+    return OT_OK;
+}
 
 int hip_fail(hipError_t e)
 {
@@ -92,7 +114,7 @@ int ensure_device(const ot_tree* t)
     t->d_src_by_level = reinterpret_cast<int32_t*>(base + off[5]);
     t->d_sched = reinterpret_cast<int32_t*>(base + off[6]);
     t->device = dev;
-    return OT_OK;
+    return resolve_static_workspace(dev);
 }
 
 int ensure_device(ot_transfer* p)
@@ -332,6 +354,22 @@ int rk_step(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, 
     if (int rc = check_step_buffers(u_zipped_dev, need / 3, workspace_dev, workspace_bytes, need)) return rc;
     if (int rc = ensure_device(tree)) return rc;
     return rk_step_launch(tree, kind, params, dt, u_zipped_dev, workspace_dev, need, static_cast<hipStream_t>(hip_stream));
+}
+
+int rk_step_static(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u_zipped_dev,
+                   void* hip_stream)
+{
+    if (!tree || !kind_ok(kind) || !params || !u_zipped_dev) return OT_E_BADARG;
+    size_t need = 0;
+    if (int rc = rk_workspace_bytes(tree, kind, &need)) return rc;
+    if (need > OT_STATIC_WORKSPACE_BYTES) return OT_E_WORKSPACE;
+    // no upload here (it allocates): the tables and the array's address must be in place already
+    if (tree->device < 0 || tree->device >= kMaxDevices) return OT_E_UNSUPPORTED;
+    if (int rc = same_device(tree->device)) return rc;
+    void* ws = g_static_ws[tree->device].load();
+    if (!ws) return OT_E_UNSUPPORTED;
+    if (int rc = check_step_buffers(u_zipped_dev, need / 3, ws, OT_STATIC_WORKSPACE_BYTES, need)) return rc;
+    return rk_step_launch(tree, kind, params, dt, u_zipped_dev, ws, need, static_cast<hipStream_t>(hip_stream));
 }
 
 int rk_centred_workspace_bytes(const ot_tree* tree, ot_rhs_kind kind, size_t* bytes)

@@ -131,6 +131,12 @@ def test_bad_arguments_are_reported_not_crashed():
         assert fn(t._h, octfd.WAVE, C.byref(rp), 0.1, C.c_void_p((1 << 32) + need - 256), ws, need, None) == octfd.OT_E_BADARG   # u begins inside the workspace
         assert fn(t._h, octfd.WAVE, C.byref(rp), 0.1, C.c_void_p((1 << 32) - 256), ws, need, None) == octfd.OT_E_BADARG          # u ends inside it
     assert L.unzip(t._h, 1, C.c_void_p(4100), C.c_void_p(8192), None) == octfd.OT_E_BADARG
+    # the static-workspace step refuses a tree whose tables are not on the device, and a step that does not fit
+    assert L.rk_step_static(t._h, octfd.WAVE, C.byref(rp), 0.1, u, None) == octfd.OT_E_UNSUPPORTED
+    assert L.rk_step_static(t._h, octfd.SYN24, C.byref(rp), 0.1, u, None) == octfd.OT_E_UNSUPPORTED   # 151 MB: fits, but not uploaded
+    t4 = octfd.Tree.build(4, 4, np.zeros((0, 3), np.uint32), np.zeros(0, np.uint32))
+    assert t4.rk_workspace_bytes(octfd.SYN24) > octfd.STATIC_WORKSPACE_BYTES
+    assert L.rk_step_static(t4._h, octfd.SYN24, C.byref(rp), 0.1, u, None) == octfd.OT_E_WORKSPACE
 
 
 def test_radii_beyond_the_cube_are_refused(orc):

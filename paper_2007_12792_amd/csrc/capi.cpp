@@ -23,7 +23,13 @@ struct ot_tree {
     mutable int32_t* d_src_slot = nullptr;
     mutable int32_t* d_src_by_level = nullptr;
     mutable int32_t* d_sched = nullptr;
+    mutable int32_t* d_vsrc = nullptr;
+    mutable int32_t* d_ghost_v = nullptr;
     mutable int device = -1;   // device the tables live on, -1 = not uploaded
+    // virtual blocks of the input of rhs_eval_zipped, which has no workspace argument: allocated by its first
+    // call that needs them (24-field system on a tree with level jumps), kept until octree_free
+    mutable double* d_virt = nullptr;
+    mutable size_t virt_bytes = 0;
 };
 
 struct ot_transfer {
@@ -90,12 +96,13 @@ int ensure_device(const ot_tree* t)
     const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
     // one allocation for all tables, each part 256-byte aligned
     const HostTree& h = t->host;
-    constexpr int kParts = 7;
+    constexpr int kParts = 9;
     const void* part[kParts] = {h.leaves.data(), h.ghost.data(), h.coarse.data(), h.by_level.data(), h.src_slot.data(),
-                                h.src_by_level.data(), h.sched.data()};
+                                h.src_by_level.data(), h.sched.data(), h.vsrc.data(), h.ghost_v.data()};
     const size_t bytes[kParts] = {nl, ng, h.coarse.size() * sizeof(int32_t), h.by_level.size() * sizeof(int32_t),
                                   h.src_slot.size() * sizeof(int32_t), h.src_by_level.size() * sizeof(int32_t),
-                                  h.sched.size() * sizeof(int32_t)};
+                                  h.sched.size() * sizeof(int32_t), h.vsrc.size() * sizeof(int32_t),
+                                  h.ghost_v.size() * sizeof(int32_t)};
     size_t off[kParts + 1] = {0};
     for (int i = 0; i < kParts; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
     char* base = nullptr;
@@ -113,6 +120,8 @@ int ensure_device(const ot_tree* t)
     t->d_src_slot = reinterpret_cast<int32_t*>(base + off[4]);
     t->d_src_by_level = reinterpret_cast<int32_t*>(base + off[5]);
     t->d_sched = reinterpret_cast<int32_t*>(base + off[6]);
+    t->d_vsrc = reinterpret_cast<int32_t*>(base + off[7]);
+    t->d_ghost_v = reinterpret_cast<int32_t*>(base + off[8]);
     t->device = dev;
     return resolve_static_workspace(dev);
 }
@@ -153,10 +162,17 @@ DeviceTree dev_view(const ot_tree* t)
 {
     return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, t->d_by_level, static_cast<int64_t>(t->host.leaves.size()),
                       t->d_src_slot, t->d_src_by_level, static_cast<int64_t>(t->host.src_by_level.size()),
-                      t->d_sched, static_cast<int64_t>(t->host.sched.size())};
+                      t->d_sched, static_cast<int64_t>(t->host.sched.size()), t->d_ghost_v, t->d_vsrc, t->host.n_virt};
 }
 
 bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }
+
+// bytes of the virtual blocks of one input vector of a kind whose fused kernels read them (the 24-field system)
+size_t virtual_bytes(const ot_tree* t, int kind)
+{
+    if (kind != OT_RHS_SYN24) return 0;
+    return static_cast<size_t>(ot_rhs_nvar_in(static_cast<ot_rhs_kind>(kind))) * static_cast<size_t>(t->host.n_virt) * 512 * sizeof(double);
+}
 
 // data arrays hold doubles: anything else cannot be a valid array and would fault in the kernels
 bool aligned8(const void* p) { return reinterpret_cast<uintptr_t>(p) % 8 == 0; }
@@ -226,6 +242,7 @@ int octree_free(ot_tree* tree)
     if (tree->device >= 0) {
         hipError_t e = hipFree(tree->d_leaves);   // the tables share one allocation
         if (e != hipSuccess) rc = hip_fail(e);
+        if (tree->d_virt && (e = hipFree(tree->d_virt)) != hipSuccess) rc = hip_fail(e);
     }
     delete tree;
     return rc;
@@ -285,7 +302,7 @@ int rhs_eval(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params,
     if (!tree || !kind_ok(kind) || !params || !padded_dev || !rhs_padded_dev || !aligned8(padded_dev) || !aligned8(rhs_padded_dev))
         return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
-    RhsArgs a{padded_dev, rhs_padded_dev, nullptr, nullptr, nullptr, rhs_padded_dev, 0.0, params->ko_sigma};
+    RhsArgs a{padded_dev, rhs_padded_dev, nullptr, nullptr, nullptr, nullptr, rhs_padded_dev, 0.0, params->ko_sigma};
     hipError_t e = launch_rhs(dev_view(tree), kind, false, false, kOutPadded, a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
@@ -296,8 +313,24 @@ int rhs_eval_zipped(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* 
     if (!tree || !kind_ok(kind) || !params || !zipped_dev || !rhs_zipped_dev || !aligned8(zipped_dev) || !aligned8(rhs_zipped_dev))
         return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
-    RhsArgs a{zipped_dev, rhs_zipped_dev, nullptr, nullptr, nullptr, rhs_zipped_dev, 0.0, params->ko_sigma};
-    hipError_t e = launch_rhs(dev_view(tree), kind, true, false, kOutZipped, a, static_cast<hipStream_t>(hip_stream));
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const DeviceTree dv = dev_view(tree);
+    const size_t vbytes = virtual_bytes(tree, kind);
+    if (vbytes > tree->virt_bytes) {      // first call that needs the virtual blocks (or more of them than before)
+        hipError_t e = hipSuccess;
+        if (tree->d_virt) e = hipFree(tree->d_virt);   // synchronises with earlier work on the old array
+        tree->d_virt = nullptr;
+        tree->virt_bytes = 0;
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&tree->d_virt), vbytes);
+        if (e != hipSuccess) return hip_fail(e);
+        tree->virt_bytes = vbytes;
+    }
+    if (vbytes) {
+        hipError_t e = launch_virtual(dv, ot_rhs_nvar_in(kind), zipped_dev, tree->d_virt, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    RhsArgs a{zipped_dev, rhs_zipped_dev, nullptr, nullptr, nullptr, vbytes ? tree->d_virt : nullptr, rhs_zipped_dev, 0.0, params->ko_sigma};
+    hipError_t e = launch_rhs(dv, kind, true, false, kOutZipped, a, s);
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
@@ -305,7 +338,8 @@ int rk_workspace_bytes(const ot_tree* tree, ot_rhs_kind kind, size_t* bytes)
 {
     if (!tree || !kind_ok(kind) || !bytes) return OT_E_BADARG;
     if (ot_rhs_nvar_in(kind) != ot_rhs_nvar_out(kind)) return OT_E_UNSUPPORTED;
-    *bytes = 3 * static_cast<size_t>(ot_rhs_nvar_in(kind)) * tree->host.leaves.size() * 512 * sizeof(double);
+    // three zipped vectors, then the virtual blocks of the current stage vector
+    *bytes = 3 * static_cast<size_t>(ot_rhs_nvar_in(kind)) * tree->host.leaves.size() * 512 * sizeof(double) + virtual_bytes(tree, kind);
     return OT_OK;
 }
 
@@ -324,22 +358,27 @@ static int check_step_buffers(const double* u, size_t u_bytes, const void* ws, s
 static int rk_step_launch(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u,
                           void* workspace_dev, size_t need, hipStream_t s)
 {
-    const size_t len = need / (3 * sizeof(double));
+    const size_t vbytes = virtual_bytes(tree, kind);
+    const size_t len = (need - vbytes) / (3 * sizeof(double));
     double* acc = static_cast<double*>(workspace_dev);
     double* sa = acc + len;
     double* sb = sa + len;
+    double* virt = vbytes ? sb + len : nullptr;
     const DeviceTree dv = dev_view(tree);
     const double sg = params->ko_sigma;
     // stage vectors ping-pong between sa and sb: a stage reads ghosts of the vector it was given
     // while writing the next one, so the two must be different arrays
     const RhsArgs st[4] = {
-        {u, sa, acc, u, nullptr, sa, 0.5 * dt, sg},    // k1 = F(u):   acc = k1,        sa = u + dt/2 k1
-        {sa, sb, acc, u, nullptr, sb, 0.5 * dt, sg},   // k2 = F(sa):  acc += 2 k2,     sb = u + dt/2 k2
-        {sb, sa, acc, u, nullptr, sa, dt, sg},         // k3 = F(sb):  acc += 2 k3,     sa = u + dt k3
-        {sa, nullptr, acc, u, nullptr, sb, dt / 6.0, sg}};   // k4 = F(sa):  u += dt/6 (acc + k4); sb is free scratch
+        {u, sa, acc, u, nullptr, virt, sa, 0.5 * dt, sg},    // k1 = F(u):   acc = k1,        sa = u + dt/2 k1
+        {sa, sb, acc, u, nullptr, virt, sb, 0.5 * dt, sg},   // k2 = F(sa):  acc += 2 k2,     sb = u + dt/2 k2
+        {sb, sa, acc, u, nullptr, virt, sa, dt, sg},         // k3 = F(sb):  acc += 2 k3,     sa = u + dt k3
+        {sa, nullptr, acc, u, nullptr, virt, sb, dt / 6.0, sg}};   // k4 = F(sa):  u += dt/6 (acc + k4); sb is free scratch
     const Epilogue ep[4] = {kRkFirst, kRkMiddle, kRkMiddle, kRkLast};
     for (int i = 0; i < 4; ++i) {
-        hipError_t e = launch_rhs(dv, kind, true, false, ep[i], st[i], s);
+        // the virtual blocks of this stage's input first; the stream orders them before the stage kernel and
+        // after the previous stage's reads of the same array
+        hipError_t e = vbytes ? launch_virtual(dv, ot_rhs_nvar_in(kind), st[i].in, virt, s) : hipSuccess;
+        if (e == hipSuccess) e = launch_rhs(dv, kind, true, false, ep[i], st[i], s);
         if (e != hipSuccess) return hip_fail(e);
     }
     return OT_OK;
@@ -351,7 +390,7 @@ int rk_step(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, 
     if (!tree || !kind_ok(kind) || !params || !u_zipped_dev || !workspace_dev) return OT_E_BADARG;
     size_t need = 0;
     if (int rc = rk_workspace_bytes(tree, kind, &need)) return rc;
-    if (int rc = check_step_buffers(u_zipped_dev, need / 3, workspace_dev, workspace_bytes, need)) return rc;
+    if (int rc = check_step_buffers(u_zipped_dev, (need - virtual_bytes(tree, kind)) / 3, workspace_dev, workspace_bytes, need)) return rc;
     if (int rc = ensure_device(tree)) return rc;
     return rk_step_launch(tree, kind, params, dt, u_zipped_dev, workspace_dev, need, static_cast<hipStream_t>(hip_stream));
 }
@@ -368,7 +407,7 @@ int rk_step_static(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* p
     if (int rc = same_device(tree->device)) return rc;
     void* ws = g_static_ws[tree->device].load();
     if (!ws) return OT_E_UNSUPPORTED;
-    if (int rc = check_step_buffers(u_zipped_dev, need / 3, ws, OT_STATIC_WORKSPACE_BYTES, need)) return rc;
+    if (int rc = check_step_buffers(u_zipped_dev, (need - virtual_bytes(tree, kind)) / 3, ws, OT_STATIC_WORKSPACE_BYTES, need)) return rc;
     return rk_step_launch(tree, kind, params, dt, u_zipped_dev, ws, need, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -376,6 +415,7 @@ int rk_centred_workspace_bytes(const ot_tree* tree, ot_rhs_kind kind, size_t* by
 {
     size_t zipped3 = 0;
     if (int rc = rk_workspace_bytes(tree, kind, &zipped3)) return rc;
+    zipped3 -= virtual_bytes(tree, kind);
     // three zipped vectors, then the padded blocks of the source leaves of the current stage vector
     *bytes = zipped3 + static_cast<size_t>(ot_rhs_nvar_in(kind)) * tree->host.src_by_level.size() * 2744 * sizeof(double);
     return OT_OK;
@@ -388,6 +428,7 @@ int rk_step_centred(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* 
     size_t need = 0, zipped3 = 0;
     if (int rc = rk_centred_workspace_bytes(tree, kind, &need)) return rc;
     if (int rc = rk_workspace_bytes(tree, kind, &zipped3)) return rc;
+    zipped3 -= virtual_bytes(tree, kind);
     if (int rc = check_step_buffers(u_zipped_dev, zipped3 / 3, workspace_dev, workspace_bytes, need)) return rc;
     if (int rc = ensure_device(tree)) return rc;
     const size_t len = zipped3 / (3 * sizeof(double));
@@ -402,10 +443,10 @@ int rk_step_centred(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* 
     const double sg = params->ko_sigma;
     // per stage: the few leaves that serve as coarser sources are ghost-filled level by level into
     // `pad`; the fused stage kernel then reads everything else straight from the zipped vector
-    const RhsArgs st[4] = {{u, sa, acc, u, pad, sa, 0.5 * dt, sg},
-                           {sa, sb, acc, u, pad, sb, 0.5 * dt, sg},
-                           {sb, sa, acc, u, pad, sa, dt, sg},
-                           {sa, nullptr, acc, u, pad, sb, dt / 6.0, sg}};
+    const RhsArgs st[4] = {{u, sa, acc, u, pad, nullptr, sa, 0.5 * dt, sg},
+                           {sa, sb, acc, u, pad, nullptr, sb, 0.5 * dt, sg},
+                           {sb, sa, acc, u, pad, nullptr, sa, dt, sg},
+                           {sa, nullptr, acc, u, pad, nullptr, sb, dt / 6.0, sg}};
     const Epilogue ep[4] = {kRkFirst, kRkMiddle, kRkMiddle, kRkLast};
     for (int i = 0; i < 4; ++i) {
         hipError_t e = launch_unzip_centred(dv, tree->host.src_level_start, true, nvar, st[i].in, pad, s);

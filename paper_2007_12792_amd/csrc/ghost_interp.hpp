@@ -263,8 +263,10 @@ __device__ __forceinline__ void interp_faces_centred(double* tile, double* scrat
 //               coarser leaves.  `base` is that variable's zipped array (ZIN) or this block's padded
 //               data.  All threads call both.  commit() does NOT end with a barrier.
 // USE = how many plan entries per thread are in use (PLAN_FACE: faces only).
-template <int NPLAN, int USE, bool REG>
-__device__ __forceinline__ void prefetch(double (&v)[NPLAN], const FillPlan<NPLAN, REG>& fp, const double* __restrict__ base, int tid)
+// VIRT: plan entries with bit 0 set are offsets into vbase, that variable's virtual blocks.
+template <int NPLAN, int USE, bool VIRT = false, bool REG>
+__device__ __forceinline__ void prefetch(double (&v)[NPLAN], const FillPlan<NPLAN, REG>& fp, const double* __restrict__ base, int tid,
+                                         const double* __restrict__ vbase = nullptr)
 {
     uint32_t off[USE];
 #pragma unroll
@@ -272,7 +274,10 @@ __device__ __forceinline__ void prefetch(double (&v)[NPLAN], const FillPlan<NPLA
     // the last entry in use may reach beyond the face prefix: read element 0 instead
     if (USE == PLAN_FACE && NPLAN > PLAN_FACE && tid + (USE - 1) * NTHREADS >= NFACE) off[USE - 1] = 0;
 #pragma unroll
-    for (int m = 0; m < USE; ++m) v[m] = ldg(base, off[m]);
+    for (int m = 0; m < USE; ++m) {
+        if (VIRT) v[m] = ldg((off[m] & 1u) ? vbase : base, off[m] & ~1u);
+        else v[m] = ldg(base, off[m]);
+    }
 }
 
 // Values of the coarser face neighbours can be requested together with the tile data

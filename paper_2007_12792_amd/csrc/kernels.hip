@@ -109,6 +109,9 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND, CENTRED)) void k_rhs
     static_assert(ZIN || !CENTRED, "the centred ghost rule applies to zipped input");
     static_assert(ZIN || !SCHED, "the schedule is for zipped input");
     using L = RhsLds<KIND, ZIN>;
+    // the 24-field kernel on zipped input reads what comes from coarser leaves out of virtual blocks, filled by
+    // k_virtual before the launch: every block then runs the path without interpolation
+    constexpr bool VIRT = ZIN && !CENTRED && KIND == OT_RHS_SYN24;
     __shared__ double tiles[L::NBUF * TILE];
     __shared__ double scratch[L::NSCRATCH];
     __shared__ BlockInfo bi;
@@ -122,7 +125,7 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND, CENTRED)) void k_rhs
 
         const int tid = threadIdx.x;
         const int64_t nb = tr.nb;
-        load_block_info(bi, tr, b, tid);
+        load_block_info<VIRT>(bi, tr, b, tid);
         __syncthreads();
         if (tid == 0 && COARSE && (KIND == OT_RHS_SYN24 || CEN)) make_box_plan(bi, false);   // read only after the next barrier
 
@@ -148,12 +151,15 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND, CENTRED)) void k_rhs
         auto var_base = [&](int v) -> const double* {
             return ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK;
         };
+        auto virt_base = [&](int v) -> const double* {  // variable v's virtual blocks
+            return VIRT ? a.virt + (int64_t)v * tr.n_virt * BLK : nullptr;
+        };
         auto pad_base = [&](int v) -> const double* {   // centred rule: variable v's padded source leaves
             return CEN ? a.pad_src + (int64_t)v * tr.n_src * PBLK : nullptr;
         };
         auto stage = [&](int v) {   // bring variable v into tile buffer 0 (barrier before and after)
             __syncthreads();
-            prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(v), tid);
+            prefetch<NPLAN, PLAN_FACE, VIRT>(pv, fp, var_base(v), tid, virt_base(v));
             commit<ZIN, NPLAN, PLAN_FACE, CEN, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(v), tid, pad_base(v));
             __syncthreads();
         };
@@ -172,7 +178,7 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND, CENTRED)) void k_rhs
             emit<EPI>(a, nb, 3, b, o8, p8, p.lap, e3);
         } else if (KIND == OT_RHS_WAVE) {
             stage(0);
-            prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(1), tid);   // pi is on its way while u is differentiated
+            prefetch<NPLAN, PLAN_FACE, VIRT>(pv, fp, var_base(1), tid, virt_base(1));   // pi is on its way while u is differentiated
             const PointOps pu = point_ops<true>(tiles, c, sigma, ih, ih2);
             // the operands of the stage update are requested only now: four more values live during the stencils
             // above push the kernel over the 64 registers that let four workgroups share a compute unit, and a
@@ -223,7 +229,7 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND, CENTRED)) void k_rhs
                 constexpr int NEXT_USE = decltype(next_use)::value;
                 if (t + 1 < NSTREAM) {
                     f1 = syn24_stream(t + 1);
-                    prefetch<NPLAN, NEXT_USE>(pv, fp, var_base(f1), tid);
+                    prefetch<NPLAN, NEXT_USE, VIRT>(pv, fp, var_base(f1), tid, virt_base(f1));
                     if (ZIN && COARSE && !CEN && NEXT_USE == PLAN_FACE) coarse_prefetch(cv, bi, var_base(f1), tid);
                 }
                 l.unext = centre((f + 11) % 24);
@@ -268,11 +274,11 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND, CENTRED)) void k_rhs
 
             {   // pass 0: gradient of variable 10 only
                 const int f = syn24_stream(0), f1 = syn24_stream(1);
-                prefetch<NPLAN, PLAN_FACE>(pv, fp, var_base(f), tid);
+                prefetch<NPLAN, PLAN_FACE, VIRT>(pv, fp, var_base(f), tid, virt_base(f));
                 if (CEN) __syncthreads();            // the box plan, made by one thread, is read in this commit already
                 commit<ZIN, NPLAN, PLAN_FACE, CEN, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(f), tid, pad_base(f));
                 __syncthreads();
-                prefetch<NPLAN, PLAN_EDGE>(pv, fp, var_base(f1), tid);
+                prefetch<NPLAN, PLAN_EDGE, VIRT>(pv, fp, var_base(f1), tid, virt_base(f1));
                 nx = d1_at(tiles, c, 1, ih); ny = d1_at(tiles, c, RS, ih); nz = d1_at(tiles, c, PS, ih);
                 commit<ZIN, NPLAN, PLAN_EDGE, CEN, COARSE>(tiles + TILE, scratch, bi, fp, pv, cv, false, var_base(f1), tid, pad_base(f1));
                 __syncthreads();
@@ -288,7 +294,7 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND, CENTRED)) void k_rhs
     const int64_t q = block_of_workgroup(blockIdx.x);
     if constexpr (!SCHED) {
         if (q >= tr.nb) return;                      // uniform over the workgroup, like everything below
-        block(q, std::true_type{});
+        block(q, std::integral_constant<bool, !VIRT>{});
     } else {
         if (q >= tr.n_sched) return;
         const int32_t e = tr.sched[q];
@@ -406,6 +412,50 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const
     }
 }
 
+// Virtual blocks: workgroup r + G s fills, for variables r, r + G, ... (G = min(8, nvar), as in k_unzip), the child
+// octants of the s-th source leaf that some block needs.  A child's 8^3 points are the fine positions f = 8 o + i per
+// axis inside the leaf, interpolated x, then y, then z like any ghost point that comes from a coarser leaf, one
+// point per thread and pass.  Wavefront w holds the coarse plane cz = w: the x and y passes stay inside that plane, so
+// they need no workgroup barrier (a wavefront's LDS operations execute in order); only the z pass combines planes.
+__global__ __launch_bounds__(NTHREADS) void k_virtual(DeviceTree tr, int nvar, const double* __restrict__ zipped, double* __restrict__ virt)
+{
+    __shared__ double C[BLK], T1[BLK], T2[2][BLK], lag[36];
+    const int tid = threadIdx.x;
+    const int stride = nvar < NXCD ? nvar : NXCD;
+    const int64_t s = blockIdx.x / stride, nb = tr.nb;
+    const int v0 = (int)(blockIdx.x - s * stride);
+    const int32_t* row = tr.vsrc + s * 3;
+    const int64_t leaf = row[0], first = row[2];
+    const int mask = row[1];
+    if (tid < 36) lag[tid] = c_lag[tid];
+    const int i = tid & 7, j = (tid >> 3) & 7, k = tid >> 6;     // tid is also the point's index in its block; k = wavefront
+    double c = zipped[((int64_t)v0 * nb + leaf) * BLK + tid];
+    __syncthreads();                                             // the weights are in place
+    int n = 0;                                                   // octants done: T2 alternates between two buffers
+#pragma unroll 1
+    for (int v = v0; v < nvar; v += stride) {
+        C[tid] = c;                                              // plane k: written and read by wavefront k only
+        if (v + stride < nvar) c = zipped[((int64_t)(v + stride) * nb + leaf) * BLK + tid];
+        double* out = virt + ((int64_t)v * tr.n_virt + first) * BLK + tid;
+#pragma unroll 1
+        for (int oct = 0; oct < 8; ++oct) {
+            if (!((mask >> oct) & 1)) continue;                  // uniform
+            const int fx = NPT * (oct & 1) + i, fy = NPT * ((oct >> 1) & 1) + j, fz = NPT * (oct >> 2) + k;
+            __builtin_amdgcn_wave_barrier();
+            T1[tid] = interp_line(&C[(k * NPT + j) * NPT], 1, fx, lag);           // (cz, cy, tx)
+            __builtin_amdgcn_wave_barrier();
+            double* T = T2[n & 1];
+            T[tid] = interp_line(&T1[k * NPT * NPT + i], NPT, fy, lag);           // (cz, ty, tx)
+            // a buffer of T2 is written again two octants later, after the barrier of the octant in between, which
+            // everybody reaches only after this octant's z pass
+            __syncthreads();
+            *out = interp_line(&T[j * NPT + i], NPT * NPT, fz, lag);              // (tz, ty, tx)
+            out += BLK;
+            ++n;
+        }
+    }
+}
+
 __global__ __launch_bounds__(NTHREADS) void k_zip(int64_t nblocks, const double* __restrict__ padded, double* __restrict__ zipped)
 {
     const int tid = threadIdx.x;
@@ -418,7 +468,7 @@ __global__ __launch_bounds__(NTHREADS) void k_zip(int64_t nblocks, const double*
 template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
 hipError_t launch_one(const DeviceTree& t, const RhsArgs& a, hipStream_t s)
 {
-    if constexpr (KIND == OT_RHS_SYN24 && ZIN)
+    if constexpr (KIND == OT_RHS_SYN24 && ZIN && CENTRED)
         hipLaunchKernelGGL((k_rhs<KIND, true, EPI, CENTRED, true>), dim3(grid_for_blocks(t.n_sched)), dim3(NTHREADS), 0, s, t, a);
     else
         hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, CENTRED, false>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
@@ -438,6 +488,7 @@ hipError_t launch_kind(const DeviceTree& t, bool zin, bool centred, Epilogue ep,
         default: return hipErrorInvalidValue;
         }
     }
+    if (zin && KIND == OT_RHS_SYN24 && !a.virt && t.n_virt > 0) return hipErrorInvalidValue;
     if (!zin) {
         switch (ep) {
         case kOutPadded: return launch_one<KIND, false, kOutPadded>(t, a, s);
@@ -483,6 +534,13 @@ hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start,
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+hipError_t launch_virtual(const DeviceTree& t, int nvar, const double* zipped, double* virt, hipStream_t s)
+{
+    if (t.n_src <= 0 || t.n_virt <= 0 || nvar <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_virtual, dim3((unsigned)(t.n_src * (nvar < NXCD ? nvar : NXCD))), dim3(NTHREADS), 0, s, t, nvar, zipped, virt);
+    return hipGetLastError();
 }
 
 hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, double* zipped, hipStream_t s)

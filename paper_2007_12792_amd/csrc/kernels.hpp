@@ -20,6 +20,10 @@ struct DeviceTree {
     int64_t n_src;
     const int32_t* sched;        // [n_sched] launch order of the 24-field kernel, see HostTree::sched
     int64_t n_sched;
+    // virtual blocks (see HostTree): the ghost table that names them, and the source leaves they are children of
+    const int32_t* ghost_v;      // [nb][27][5]
+    const int32_t* vsrc;         // [n_src][3] {leaf id, mask of child octants, first virtual block}
+    int64_t n_virt;
 };
 
 // HostTree::sched is made of chunks of this many entries; the kernels hand one chunk to one XCD
@@ -42,6 +46,7 @@ struct RhsArgs {
     double* acc;        // Runge-Kutta accumulator (zipped)
     double* u;          // state at the start of the step (zipped); written by kRkLast
     const double* pad_src;   // centred ghost rule only: padded blocks of the source leaves of `in`, [V][n_src][2744]
+    const double* virt;      // the virtual blocks of `in`, [V][n_virt][512] (kernels that read ghost_v; filled by launch_virtual)
     double* stash;      // SYN24 only: array shaped like `out` whose variables 10..19 may be used as
                         // scratch until their final values are written (may be `out` itself)
     double c;           // dt/2, dt or dt/6
@@ -54,6 +59,9 @@ hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, dou
 // then refers to src_by_level), padded [nvar][n_src][2744] indexed by src_slot
 hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, bool sources_only, int nvar,
                                 const double* zipped, double* padded, hipStream_t s);
+// fills the virtual blocks of a zipped array: virt [nvar][n_virt][512], each the child octant of its source leaf,
+// every point interpolated inside that leaf exactly as a ghost point is in unzip
+hipError_t launch_virtual(const DeviceTree& t, int nvar, const double* zipped, double* virt, hipStream_t s);
 hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, double* zipped, hipStream_t s);
 // in_zipped = false: args.in is padded; true: args.in is zipped.  centred (zipped input only): ghost
 // values from coarser leaves follow the centred rule and are read from args.pad_src

@@ -278,6 +278,45 @@ void make_level_lists(HostTree& t)
     }
 }
 
+// needs src_slot (make_level_lists)
+void make_virtual_blocks(HostTree& t)
+{
+    const size_t nb = t.leaves.size();
+    const size_t n_src = t.src_by_level.size();
+    t.vsrc.assign(n_src * kVsrcRow, 0);
+    // which child octant of its parent the neighbour octant in direction dir is: the low bit of its anchor
+    auto octant_of = [&](size_t b, int dir) {
+        const ot_leaf& o = t.leaves[b];
+        const uint32_t x = o.ix + (dir % 3 - 1), y = o.iy + ((dir / 3) % 3 - 1), z = o.iz + (dir / 9 - 1);   // mod 2^l keeps the low bit
+        return static_cast<int>((x & 1) | ((y & 1) << 1) | ((z & 1) << 2));
+    };
+    for (size_t b = 0; b < nb; ++b) {
+        const int32_t slot = t.src_slot[b];
+        if (slot >= 0) t.vsrc[slot * kVsrcRow] = static_cast<int32_t>(b);
+    }
+    for (size_t b = 0; b < nb; ++b)
+        for (int dir = 0; dir < kDirs; ++dir) {
+            const int32_t* e = &t.ghost[(b * kDirs + dir) * kEntry];
+            if (e[0] == kCoarser) t.vsrc[t.src_slot[e[1]] * kVsrcRow + 1] |= 1 << octant_of(b, dir);
+        }
+    int32_t n = 0;
+    for (size_t s = 0; s < n_src; ++s) {
+        t.vsrc[s * kVsrcRow + 2] = n;
+        n += __builtin_popcount(static_cast<unsigned>(t.vsrc[s * kVsrcRow + 1]));
+    }
+    t.n_virt = n;
+    t.ghost_v = t.ghost;
+    for (size_t b = 0; b < nb; ++b)
+        for (int dir = 0; dir < kDirs; ++dir) {
+            int32_t* e = &t.ghost_v[(b * kDirs + dir) * kEntry];
+            if (e[0] != kCoarser) continue;
+            const int32_t* row = &t.vsrc[t.src_slot[e[1]] * kVsrcRow];
+            const int c = octant_of(b, dir);
+            e[0] = kVirtual;
+            e[1] = row[2] + __builtin_popcount(static_cast<unsigned>(row[1]) & ((1u << c) - 1));
+        }
+}
+
 int build_tree(const ot_build_params& p, HostTree& out)
 {
     if (p.lmin < 3 || p.lmax < p.lmin || p.lmax > 19) return OT_E_BADARG;
@@ -308,7 +347,7 @@ int build_tree(const ot_build_params& p, HostTree& out)
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
     const int rc = make_ghost_table(t, out.leaves, out.ghost);
-    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); }
+    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); make_virtual_blocks(out); }
     return rc;
 }
 
@@ -335,7 +374,7 @@ int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out)
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
     const int rc = make_ghost_table(t, out.leaves, out.ghost);
-    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); }
+    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); make_virtual_blocks(out); }
     return rc;
 }
 

@@ -11,7 +11,8 @@ namespace octfd {
 constexpr int kDirs = 27;          // directions (dz+1)*9 + (dy+1)*3 + (dx+1)
 constexpr int kEntry = 5;          // {kind, id0..id3}
 constexpr int kCoarseRow = 32;     // ints per block in HostTree::coarse
-enum GhostKind : int32_t { kSame = 0, kFiner = 1, kCoarser = 2 };
+enum GhostKind : int32_t { kSame = 0, kFiner = 1, kCoarser = 2, kVirtual = 3 };
+constexpr int kVsrcRow = 3;        // ints per source leaf in HostTree::vsrc
 
 struct HostTree {
     std::vector<ot_leaf> leaves;   // Morton order
@@ -43,6 +44,18 @@ struct HostTree {
     // together from the first to the last workgroup and every XCD (which receives every kSchedXcds-th chunk)
     // meets them in the same order.  Entry = block id, | kSchedCoarse for the second part.
     std::vector<int32_t> sched;
+    // "Virtual blocks".  Where the same-level neighbour octant of a block does not exist because its parent L is
+    // a leaf, the ghost values in that direction are interpolated inside L, and what they are depends only on L's
+    // data and on the fine position inside L, not on which block asks.  Such an octant can therefore be filled
+    // once, all 8^3 points of it, like a child of L ("virtual block"), after which the blocks around it read it
+    // exactly like a neighbour of their own level.
+    //   vsrc    [n_src][kVsrcRow]  per source leaf, in Morton order: {leaf id, mask of the child octants
+    //                              (bit ox | oy<<1 | oz<<2) that some block needs, index of its first virtual block};
+    //                              a leaf's virtual blocks are numbered consecutively in ascending octant order
+    //   ghost_v [nb][27][5]        the ghost table with every coarser entry replaced by {kVirtual, virtual block}
+    //   n_virt                     number of virtual blocks
+    std::vector<int32_t> vsrc, ghost_v;
+    int64_t n_virt = 0;
 };
 
 // Each returns an OT_* status.
@@ -50,5 +63,6 @@ int build_tree(const ot_build_params& p, HostTree& out);
 int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out);
 void make_coarse_sources(HostTree& t);
 void make_level_lists(HostTree& t);
+void make_virtual_blocks(HostTree& t);
 
 }  // namespace octfd

@@ -10,7 +10,7 @@ namespace {
 
 constexpr int NPT = 8, PAD = 3, NP = 14, BLK = 512, PBLK = 2744;
 constexpr int NTHREADS = 512;
-constexpr int K_COARSER = 2, K_SAME = 0;
+constexpr int K_COARSER = 2, K_SAME = 0, K_VIRT = 3;
 
 // LDS geometry (in doubles).  Rows are stored compactly (stride 14) and planes are padded to a
 // stride of 200 = 8 (mod 32).  A wavefront holds one j row of the block, its lanes run over
@@ -98,9 +98,11 @@ inline unsigned grid_for_blocks(int64_t nb)
     return (unsigned)((nb + span - 1) / span * span);
 }
 
+// VIRT: the ghost table in which coarser neighbours appear as virtual blocks
+template <bool VIRT = false>
 __device__ __forceinline__ void load_block_info(BlockInfo& bi, const DeviceTree& tr, int64_t b, int tid)
 {
-    if (tid < 27 * 5) bi.gt[tid] = tr.ghost[b * (27 * 5) + tid];
+    if (tid < 27 * 5) bi.gt[tid] = (VIRT ? tr.ghost_v : tr.ghost)[b * (27 * 5) + tid];
     if (tid >= 192 && tid < 192 + 36) bi.lag[tid - 192] = c_lag[tid - 192];
     if (tid >= 256 && tid < 256 + 32) bi.cs[tid - 256] = tr.coarse[b * 32 + (tid - 256)];
     if (tid >= 384 && tid < 384 + 8) {
@@ -180,7 +182,10 @@ static_assert(SCRATCH >= 1024 + 2 * 512, "face interpolation staging: 8 x 128 pe
 
 // Source of every padded point this thread fills, as a byte offset into one variable's zipped
 // array (same-level copy or injection from a finer leaf).  Points whose source is coarser are left
-// to the interpolation passes.  NPOINTS = how long a prefix of the enumeration is planned.
+// to the interpolation passes; with the ghost table that names virtual blocks there are none, and a
+// point inside a virtual block is a same-level copy out of the array of virtual blocks: byte offset
+// into one variable's part of that array, marked by bit 0 (offsets are multiples of 8).
+// NPOINTS = how long a prefix of the enumeration is planned.
 template <int NPLAN, int NPOINTS, bool REG>
 __device__ __forceinline__ void make_plan_zipped(FillPlan<NPLAN, REG>& fp, const BlockInfo& bi, int tid)
 {
@@ -202,7 +207,7 @@ __device__ __forceinline__ void make_plan_zipped(FillPlan<NPLAN, REG>& fp, const
                 const int lx = ii - PAD + (1 - rx) * NPT, ly = jj - PAD + (1 - ry) * NPT, lz = kk - PAD + (1 - rz) * NPT;
                 dst = tidx(kk, jj, ii);
                 uint32_t elem;
-                if (kind == K_SAME) {
+                if (kind == K_SAME || kind == K_VIRT) {
                     elem = (uint32_t)e[1] * BLK + (lz * NPT + ly) * NPT + lx;
                 } else {
                     // which child holds the point: forced by the direction on non-free axes
@@ -215,7 +220,7 @@ __device__ __forceinline__ void make_plan_zipped(FillPlan<NPLAN, REG>& fp, const
                     if (rz == 1) { q |= bz << sh; }
                     elem = (uint32_t)e[1 + q] * BLK + ((2 * lz - NPT * bz) * NPT + (2 * ly - NPT * by)) * NPT + (2 * lx - NPT * bx);
                 }
-                src = elem * 8u;
+                src = elem * 8u | (kind == K_VIRT ? 1u : 0u);
             }
         }
         fp.set_src(m, tid, src);

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liboctfd.so")
-SOURCES = ["capi.cpp", "octree_host.cpp", "transfer_host.cpp", "kernels.hip", "transfer.hip"]
+SOURCES = ["capi.cpp", "octree_host.cpp", "transfer_host.cpp", "kernels.hip", "pair.hip", "transfer.hip"]
 
 
 def hipcc():

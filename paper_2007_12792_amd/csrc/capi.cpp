@@ -25,6 +25,8 @@ struct ot_tree {
     mutable int32_t* d_sched = nullptr;
     mutable int32_t* d_vsrc = nullptr;
     mutable int32_t* d_ghost_v = nullptr;
+    mutable int32_t* d_pairs = nullptr;
+    mutable int32_t* d_singles = nullptr;
     mutable int device = -1;   // device the tables live on, -1 = not uploaded
     // virtual blocks of the input of rhs_eval_zipped, which has no workspace argument: allocated by its first
     // call that needs them (24-field system on a tree with level jumps), kept until octree_free
@@ -96,13 +98,13 @@ int ensure_device(const ot_tree* t)
     const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
     // one allocation for all tables, each part 256-byte aligned
     const HostTree& h = t->host;
-    constexpr int kParts = 9;
+    constexpr int kParts = 11;
     const void* part[kParts] = {h.leaves.data(), h.ghost.data(), h.coarse.data(), h.by_level.data(), h.src_slot.data(),
-                                h.src_by_level.data(), h.sched.data(), h.vsrc.data(), h.ghost_v.data()};
+                                h.src_by_level.data(), h.sched.data(), h.vsrc.data(), h.ghost_v.data(), h.pairs.data(), h.singles.data()};
     const size_t bytes[kParts] = {nl, ng, h.coarse.size() * sizeof(int32_t), h.by_level.size() * sizeof(int32_t),
                                   h.src_slot.size() * sizeof(int32_t), h.src_by_level.size() * sizeof(int32_t),
                                   h.sched.size() * sizeof(int32_t), h.vsrc.size() * sizeof(int32_t),
-                                  h.ghost_v.size() * sizeof(int32_t)};
+                                  h.ghost_v.size() * sizeof(int32_t), h.pairs.size() * sizeof(int32_t), h.singles.size() * sizeof(int32_t)};
     size_t off[kParts + 1] = {0};
     for (int i = 0; i < kParts; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
     char* base = nullptr;
@@ -122,6 +124,8 @@ int ensure_device(const ot_tree* t)
     t->d_sched = reinterpret_cast<int32_t*>(base + off[6]);
     t->d_vsrc = reinterpret_cast<int32_t*>(base + off[7]);
     t->d_ghost_v = reinterpret_cast<int32_t*>(base + off[8]);
+    t->d_pairs = reinterpret_cast<int32_t*>(base + off[9]);
+    t->d_singles = reinterpret_cast<int32_t*>(base + off[10]);
     t->device = dev;
     return resolve_static_workspace(dev);
 }
@@ -162,7 +166,8 @@ DeviceTree dev_view(const ot_tree* t)
 {
     return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, t->d_by_level, static_cast<int64_t>(t->host.leaves.size()),
                       t->d_src_slot, t->d_src_by_level, static_cast<int64_t>(t->host.src_by_level.size()),
-                      t->d_sched, static_cast<int64_t>(t->host.sched.size()), t->d_ghost_v, t->d_vsrc, t->host.n_virt};
+                      t->d_sched, static_cast<int64_t>(t->host.sched.size()), t->d_ghost_v, t->d_vsrc, t->host.n_virt,
+                      t->d_pairs, static_cast<int64_t>(t->host.pairs.size()), t->d_singles, static_cast<int64_t>(t->host.singles.size())};
 }
 
 bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }

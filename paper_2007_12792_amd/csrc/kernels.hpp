@@ -24,6 +24,12 @@ struct DeviceTree {
     const int32_t* ghost_v;      // [nb][27][5]
     const int32_t* vsrc;         // [n_src][3] {leaf id, mask of child octants, first virtual block}
     int64_t n_virt;
+    // the 24-field system on zipped input: sibling pairs (first block of each) for the two-block kernel, and the
+    // remaining blocks, which run the one-block kernel
+    const int32_t* pairs;
+    int64_t n_pairs;
+    const int32_t* singles;
+    int64_t n_singles;
 };
 
 // HostTree::sched is made of chunks of this many entries; the kernels hand one chunk to one XCD
@@ -63,6 +69,9 @@ hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start,
 // every point interpolated inside that leaf exactly as a ghost point is in unzip
 hipError_t launch_virtual(const DeviceTree& t, int nvar, const double* zipped, double* virt, hipStream_t s);
 hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, double* zipped, hipStream_t s);
+// the 24-field right-hand side on the sibling pairs of the tree (pair.hip): zipped input with its virtual blocks,
+// epilogue kOutZipped or one of the Runge-Kutta stages
+hipError_t launch_rhs_pairs(const DeviceTree& t, Epilogue ep, const RhsArgs& args, const int32_t* pairs, int64_t npairs, hipStream_t s);
 // in_zipped = false: args.in is padded; true: args.in is zipped.  centred (zipped input only): ghost
 // values from coarser leaves follow the centred rule and are read from args.pad_src
 hipError_t launch_rhs(const DeviceTree& t, ot_rhs_kind kind, bool in_zipped, bool centred, Epilogue ep,

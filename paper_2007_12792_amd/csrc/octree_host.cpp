@@ -317,6 +317,26 @@ void make_virtual_blocks(HostTree& t)
         }
 }
 
+void make_pairs(HostTree& t)
+{
+    const size_t nb = t.leaves.size();
+    t.pairs.clear();
+    t.singles.clear();
+    for (size_t b = 0; b < nb;) {
+        const ot_leaf& o = t.leaves[b];
+        if (b + 1 < nb && !(o.ix & 1)) {
+            const ot_leaf& n = t.leaves[b + 1];
+            if (n.level == o.level && n.ix == o.ix + 1 && n.iy == o.iy && n.iz == o.iz) {
+                t.pairs.push_back(static_cast<int32_t>(b));
+                b += 2;
+                continue;
+            }
+        }
+        t.singles.push_back(static_cast<int32_t>(b));
+        ++b;
+    }
+}
+
 int build_tree(const ot_build_params& p, HostTree& out)
 {
     if (p.lmin < 3 || p.lmax < p.lmin || p.lmax > 19) return OT_E_BADARG;
@@ -347,7 +367,7 @@ int build_tree(const ot_build_params& p, HostTree& out)
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
     const int rc = make_ghost_table(t, out.leaves, out.ghost);
-    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); make_virtual_blocks(out); }
+    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); make_virtual_blocks(out); make_pairs(out); }
     return rc;
 }
 
@@ -374,7 +394,7 @@ int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out)
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
     const int rc = make_ghost_table(t, out.leaves, out.ghost);
-    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); make_virtual_blocks(out); }
+    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); make_virtual_blocks(out); make_pairs(out); }
     return rc;
 }
 

@@ -56,6 +56,11 @@ struct HostTree {
     //   n_virt                     number of virtual blocks
     std::vector<int32_t> vsrc, ghost_v;
     int64_t n_virt = 0;
+    // Sibling pairs for the two-block kernel of the 24-field system: `pairs` lists the first block of every two
+    // leaves that are the lower and upper x child of one parent (they follow each other in Morton order), `singles`
+    // every other block (a leaf whose x sibling is subdivided).  Both in Morton order; together they cover every
+    // block exactly once.
+    std::vector<int32_t> pairs, singles;
 };
 
 // Each returns an OT_* status.
@@ -64,5 +69,6 @@ int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out);
 void make_coarse_sources(HostTree& t);
 void make_level_lists(HostTree& t);
 void make_virtual_blocks(HostTree& t);
+void make_pairs(HostTree& t);
 
 }  // namespace octfd

@@ -180,6 +180,29 @@ struct FillPlan {
 static_assert(TILE < 65536, "tile indices are packed in pairs");
 static_assert(SCRATCH >= 1024 + 2 * 512, "face interpolation staging: 8 x 128 per-wavefront + 2 x 512 shared");
 
+// Where the point (lx, ly, lz) of the same-level octant in direction (rx, ry, rz) - 1 comes from, given that
+// direction's table entry e (not a coarser one): byte offset into one variable's zipped array (same level: copy;
+// finer: the coinciding node of the child that holds it) or, marked by bit 0, into its array of virtual blocks.
+__device__ __forceinline__ uint32_t ghost_source(const int32_t* e, int rx, int ry, int rz, int lx, int ly, int lz)
+{
+    const int kind = e[0];
+    uint32_t elem;
+    if (kind == K_SAME || kind == K_VIRT) {
+        elem = (uint32_t)e[1] * BLK + (lz * NPT + ly) * NPT + lx;
+    } else {
+        // which child holds the point: forced by the direction on non-free axes
+        const int bx = rx == 1 ? (lx >> 2) : (rx == 0 ? 1 : 0);
+        const int by = ry == 1 ? (ly >> 2) : (ry == 0 ? 1 : 0);
+        const int bz = rz == 1 ? (lz >> 2) : (rz == 0 ? 1 : 0);
+        int q = 0, sh = 0;
+        if (rx == 1) { q |= bx << sh; ++sh; }
+        if (ry == 1) { q |= by << sh; ++sh; }
+        if (rz == 1) { q |= bz << sh; }
+        elem = (uint32_t)e[1 + q] * BLK + ((2 * lz - NPT * bz) * NPT + (2 * ly - NPT * by)) * NPT + (2 * lx - NPT * bx);
+    }
+    return elem * 8u | (kind == K_VIRT ? 1u : 0u);
+}
+
 // Source of every padded point this thread fills, as a byte offset into one variable's zipped
 // array (same-level copy or injection from a finer leaf).  Points whose source is coarser are left
 // to the interpolation passes; with the ghost table that names virtual blocks there are none, and a
@@ -201,26 +224,11 @@ __device__ __forceinline__ void make_plan_zipped(FillPlan<NPLAN, REG>& fp, const
             const int ry = jj < PAD ? 0 : (jj < PAD + NPT ? 1 : 2);
             const int rz = kk < PAD ? 0 : (kk < PAD + NPT ? 1 : 2);
             const int32_t* e = &bi.gt[(rz * 9 + ry * 3 + rx) * 5];
-            const int kind = e[0];
-            if (kind != K_COARSER) {
+            if (e[0] != K_COARSER) {
                 // coordinates inside the neighbouring octant of the same level, 0..7
                 const int lx = ii - PAD + (1 - rx) * NPT, ly = jj - PAD + (1 - ry) * NPT, lz = kk - PAD + (1 - rz) * NPT;
                 dst = tidx(kk, jj, ii);
-                uint32_t elem;
-                if (kind == K_SAME || kind == K_VIRT) {
-                    elem = (uint32_t)e[1] * BLK + (lz * NPT + ly) * NPT + lx;
-                } else {
-                    // which child holds the point: forced by the direction on non-free axes
-                    const int bx = rx == 1 ? (lx >> 2) : (rx == 0 ? 1 : 0);
-                    const int by = ry == 1 ? (ly >> 2) : (ry == 0 ? 1 : 0);
-                    const int bz = rz == 1 ? (lz >> 2) : (rz == 0 ? 1 : 0);
-                    int q = 0, sh = 0;
-                    if (rx == 1) { q |= bx << sh; ++sh; }
-                    if (ry == 1) { q |= by << sh; ++sh; }
-                    if (rz == 1) { q |= bz << sh; }
-                    elem = (uint32_t)e[1 + q] * BLK + ((2 * lz - NPT * bz) * NPT + (2 * ly - NPT * by)) * NPT + (2 * lx - NPT * bx);
-                }
-                src = elem * 8u | (kind == K_VIRT ? 1u : 0u);
+                src = ghost_source(e, rx, ry, rz, lx, ly, lz);
             }
         }
         fp.set_src(m, tid, src);

@@ -24,6 +24,7 @@ struct ot_tree {
     mutable int32_t* d_src_by_level = nullptr;
     mutable int32_t* d_sched = nullptr;
     mutable int32_t* d_vsrc = nullptr;
+    mutable int32_t* d_vblk = nullptr;
     mutable int32_t* d_ghost_v = nullptr;
     mutable int32_t* d_pairs = nullptr;
     mutable int32_t* d_singles = nullptr;
@@ -98,13 +99,14 @@ int ensure_device(const ot_tree* t)
     const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
     // one allocation for all tables, each part 256-byte aligned
     const HostTree& h = t->host;
-    constexpr int kParts = 11;
+    constexpr int kParts = 12;
     const void* part[kParts] = {h.leaves.data(), h.ghost.data(), h.coarse.data(), h.by_level.data(), h.src_slot.data(),
-                                h.src_by_level.data(), h.sched.data(), h.vsrc.data(), h.ghost_v.data(), h.pairs.data(), h.singles.data()};
+                                h.src_by_level.data(), h.sched.data(), h.vsrc.data(), h.ghost_v.data(), h.pairs.data(), h.singles.data(), h.vblk.data()};
     const size_t bytes[kParts] = {nl, ng, h.coarse.size() * sizeof(int32_t), h.by_level.size() * sizeof(int32_t),
                                   h.src_slot.size() * sizeof(int32_t), h.src_by_level.size() * sizeof(int32_t),
                                   h.sched.size() * sizeof(int32_t), h.vsrc.size() * sizeof(int32_t),
-                                  h.ghost_v.size() * sizeof(int32_t), h.pairs.size() * sizeof(int32_t), h.singles.size() * sizeof(int32_t)};
+                                  h.ghost_v.size() * sizeof(int32_t), h.pairs.size() * sizeof(int32_t), h.singles.size() * sizeof(int32_t),
+                                  h.vblk.size() * sizeof(int32_t)};
     size_t off[kParts + 1] = {0};
     for (int i = 0; i < kParts; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
     char* base = nullptr;
@@ -126,6 +128,7 @@ int ensure_device(const ot_tree* t)
     t->d_ghost_v = reinterpret_cast<int32_t*>(base + off[8]);
     t->d_pairs = reinterpret_cast<int32_t*>(base + off[9]);
     t->d_singles = reinterpret_cast<int32_t*>(base + off[10]);
+    t->d_vblk = reinterpret_cast<int32_t*>(base + off[11]);
     t->device = dev;
     return resolve_static_workspace(dev);
 }
@@ -166,7 +169,7 @@ DeviceTree dev_view(const ot_tree* t)
 {
     return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, t->d_by_level, static_cast<int64_t>(t->host.leaves.size()),
                       t->d_src_slot, t->d_src_by_level, static_cast<int64_t>(t->host.src_by_level.size()),
-                      t->d_sched, static_cast<int64_t>(t->host.sched.size()), t->d_ghost_v, t->d_vsrc, t->host.n_virt,
+                      t->d_sched, static_cast<int64_t>(t->host.sched.size()), t->d_ghost_v, t->d_vsrc, t->d_vblk, t->host.n_virt,
                       t->d_pairs, static_cast<int64_t>(t->host.pairs.size()), t->d_singles, static_cast<int64_t>(t->host.singles.size())};
 }
 

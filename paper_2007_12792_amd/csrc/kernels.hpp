@@ -23,6 +23,7 @@ struct DeviceTree {
     // virtual blocks (see HostTree): the ghost table that names them, and the source leaves they are children of
     const int32_t* ghost_v;      // [nb][27][5]
     const int32_t* vsrc;         // [n_src][3] {leaf id, mask of child octants, first virtual block}
+    const int32_t* vblk;         // [n_virt][2] {source leaf, child octant} of every virtual block
     int64_t n_virt;
     // the 24-field system on zipped input: sibling pairs (first block of each) for the two-block kernel, and the
     // remaining blocks, which run the one-block kernel

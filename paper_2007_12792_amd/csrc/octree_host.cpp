@@ -305,6 +305,14 @@ void make_virtual_blocks(HostTree& t)
         n += __builtin_popcount(static_cast<unsigned>(t.vsrc[s * kVsrcRow + 1]));
     }
     t.n_virt = n;
+    t.vblk.clear();
+    t.vblk.reserve(2 * static_cast<size_t>(n));
+    for (size_t s = 0; s < n_src; ++s)
+        for (int c = 0; c < 8; ++c)
+            if ((t.vsrc[s * kVsrcRow + 1] >> c) & 1) {
+                t.vblk.push_back(t.vsrc[s * kVsrcRow]);
+                t.vblk.push_back(c);
+            }
     t.ghost_v = t.ghost;
     for (size_t b = 0; b < nb; ++b)
         for (int dir = 0; dir < kDirs; ++dir) {

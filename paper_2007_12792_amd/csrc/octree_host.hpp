@@ -52,9 +52,10 @@ struct HostTree {
     //   vsrc    [n_src][kVsrcRow]  per source leaf, in Morton order: {leaf id, mask of the child octants
     //                              (bit ox | oy<<1 | oz<<2) that some block needs, index of its first virtual block};
     //                              a leaf's virtual blocks are numbered consecutively in ascending octant order
+    //   vblk    [n_virt][2]        per virtual block {source leaf id, child octant}
     //   ghost_v [nb][27][5]        the ghost table with every coarser entry replaced by {kVirtual, virtual block}
     //   n_virt                     number of virtual blocks
-    std::vector<int32_t> vsrc, ghost_v;
+    std::vector<int32_t> vsrc, vblk, ghost_v;
     int64_t n_virt = 0;
     // Sibling pairs for the two-block kernel of the 24-field system: `pairs` lists the first block of every two
     // leaves that are the lower and upper x child of one parent (they follow each other in Morton order), `singles`

@@ -40,7 +40,8 @@ constexpr int NGF = 2 * PAD * NPT * NPT + 4 * PAD * 2 * NPT * NPT;              
 constexpr int NGE = NGF + 8 * PAD * PAD * NPT + 4 * PAD * PAD * 2 * NPT;           // 3072 = 3 * NT
 constexpr int USE_FACE = 2, USE_EDGE = 3;                                          // plan entries per thread in use
 static_assert(NGE == 3 * NT && NGF <= 2 * NT, "plan entries per thread");
-constexpr int PAIR_CHUNK = kSchedChunk / 2;   // pairs per chunk: the same 16 blocks as a chunk of the one-block kernel
+constexpr int PAIR_CHUNK = 32;           // pairs per chunk: the 32 workgroups that run on an XCD at a time take 64 consecutive blocks
+                                         // (measured on the 102,075-block tree: 59.6 / 58.8 / 58.3 / 57.9 / 57.8 ms per step for 1 / 4 / 8 / 16 / 32)
 
 __device__ __forceinline__ int gx(int g) { return g < PAD ? g : g + 2 * NPT; }     // 0,1,2,19,20,21
 __device__ __forceinline__ int gyz(int g) { return g < PAD ? g : g + NPT; }        // 0,1,2,11,12,13
@@ -112,9 +113,12 @@ template <int EPI>
 __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, const int32_t* __restrict__ pairs, int64_t npairs)
 {
     __shared__ double tile[pr::TILE];
-    __shared__ double wz[pr::WZ];
-    __shared__ double wy[pr::WY];
-    __shared__ double lapS[10 * pr::NT];                 // Lap_s of the thread's point at lapS[s * pr::NT + tid]
+    __shared__ double wyz[pr::WZ + pr::WY];          // D1_z u and D1_y u during the second-derivative passes
+    __shared__ double lapS[10 * pr::NT];             // Lap_s of the thread's point at lapS[s * pr::NT + tid]
+    __shared__ double keep10[pr::NT];                // u_10 at the thread's point, from pass 0 to the pass over variable 23
+    double* const wz = wyz;
+    double* const wy = wyz + pr::WZ;
+    static_assert(3 * pr::NT <= pr::WZ + pr::WY, "u_23, u_22, u_21 are kept in the idle D1 arrays");
     __shared__ int32_t gt[2 * 27 * 5];               // table rows of the two blocks
     __shared__ uint32_t s_level;
 
@@ -186,7 +190,12 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, c
     using UseEdge = std::integral_constant<int, pr::USE_EDGE>;
     using UseFace = std::integral_constant<int, pr::USE_FACE>;
 
-    const double halpha = 0.5 * centre(0), bx = centre(1), by = centre(2), bz = centre(3);
+    // Point-wise factors.  alpha and beta are kept as the fields' own values u_0..u_3, so that the same registers also
+    // serve as the operand u_{a+11} of the passes a = 13..16.  The other passes that need a variable already seen take
+    // it from LDS where there is room (u_10 from pass 0; u_23, u_22, u_21 from the passes over them, parked in the D1
+    // arrays, which are idle by then); the passes a = 0..9, whose operand comes later in the stream, and a = 17..22
+    // (u_4..u_9, which live on only as G) read it from memory.
+    const double u0 = centre(0), bx = centre(1), by = centre(2), bz = centre(3);
     const double Gxx = 1.0 - 0.125 * centre(4), Gxy = -(0.125 * centre(5)), Gxz = -(0.125 * centre(6));
     const double Gyy = 1.0 - 0.125 * centre(7), Gyz = -(0.125 * centre(8)), Gzz = 1.0 - 0.125 * centre(9);
     double nx = 0, ny = 0, nz = 0;
@@ -199,6 +208,7 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, c
         commit(nxt, UseFace{});
         __syncthreads();
         prefetch(nxt, f1, UseEdge{});
+        keep10[tid] = tile[c];
         nx = d1_at(tile, c, 1, ih); ny = d1_at(tile, c, pr::RS, ih); nz = d1_at(tile, c, pr::PS, ih);
         __syncthreads();                             // everybody is done with the tile
         commit(nxt, UseEdge{});
@@ -220,29 +230,39 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, c
         off = fma(Gyz, mx.dyz, off);
         const double lap = fma(2.0, off, p.diag);
         lapS[f * pr::NT + tid] = lap;
-        emit<EPI>(a, nb, f, b0, o8, 0u, syn24_combine(p, f, lap, halpha, unext), eo);
+        emit<EPI>(a, nb, f, b0, o8, 0u, syn24_combine(p, f, lap, 0.5 * u0, unext), eo);
         commit(nxt, next_use);
         __syncthreads();                             // the tile is complete; D1_y u, D1_z u may be overwritten
     };
 #pragma unroll 1
     for (int t = 1; t < 10; ++t) pass_d2(t, UseEdge{});
     pass_d2(10, UseFace{});
-    // passes over the variables without second derivatives (23..10)
-#pragma unroll 1
-    for (int t = 11; t < NSTREAM; ++t) {
+    // passes over the variables without second derivatives (23..10); `unext` = u_{a+11} at the thread's point
+    auto pass_light = [&](int t, double unext) {
         const int f = syn24_stream(t);
         const bool more = t + 1 < NSTREAM;
         if (more) prefetch(nxt, syn24_stream(t + 1), UseFace{});
-        const double unext = centre((f + 11) % 24);
         const EpiOperands eo = epi_prefetch<EPI>(a, nb, f, o8);
+        if (t <= 13) wyz[(t - 11) * pr::NT + tid] = tile[c];     // u_23, u_22, u_21 for the last three passes
         const Syn24Part p = syn24_axes<false, pr::RS, pr::PS>(tile, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
-        emit<EPI>(a, nb, f, b0, o8, 0u, syn24_combine(p, f, lapS[(f % 10) * pr::NT + tid], halpha, unext), eo);
+        emit<EPI>(a, nb, f, b0, o8, 0u, syn24_combine(p, f, lapS[(f % 10) * pr::NT + tid], 0.5 * u0, unext), eo);
         if (more) {
             __syncthreads();                         // everybody is done with the tile
             commit(nxt, UseFace{});
             __syncthreads();
         }
-    }
+    };
+    // u_{a+11}: a = 23 -> u_10 (LDS); a = 22..17 -> u_9..u_4 (memory); a = 16..13 -> u_3..u_0 (registers);
+    // a = 12, 11, 10 -> u_23, u_22, u_21 (LDS)
+    pass_light(11, keep10[tid]);
+#pragma unroll 1
+    for (int t = 12; t <= 17; ++t) pass_light(t, centre(21 - t));
+    pass_light(18, bz);
+    pass_light(19, by);
+    pass_light(20, bx);
+    pass_light(21, u0);
+#pragma unroll 1
+    for (int t = 22; t < NSTREAM; ++t) pass_light(t, wyz[(t - 22) * pr::NT + tid]);
 }
 
 }  // namespace

@@ -16,21 +16,11 @@ using namespace octfd;
 // as const and fill the cache on first use (octree_upload fills it ahead of time).
 struct ot_tree {
     HostTree host;
-    mutable ot_leaf* d_leaves = nullptr;
-    mutable int32_t* d_ghost = nullptr;
-    mutable int32_t* d_coarse = nullptr;
-    mutable int32_t* d_by_level = nullptr;
-    mutable int32_t* d_src_slot = nullptr;
-    mutable int32_t* d_src_by_level = nullptr;
-    mutable int32_t* d_sched = nullptr;
-    mutable int32_t* d_vsrc = nullptr;
-    mutable int32_t* d_vblk = nullptr;
-    mutable int32_t* d_ghost_v = nullptr;
-    mutable int32_t* d_pairs = nullptr;
-    mutable int32_t* d_singles = nullptr;
-    mutable int device = -1;   // device the tables live on, -1 = not uploaded
+    mutable char* d_base = nullptr;    // one allocation for all tables
+    mutable DeviceTree dev{};          // views into it
+    mutable int device = -1;           // device the tables live on, -1 = not uploaded
     // virtual blocks of the input of rhs_eval_zipped, which has no workspace argument: allocated by its first
-    // call that needs them (24-field system on a tree with level jumps), kept until octree_free
+    // call that needs them (a tree with level jumps), kept until octree_free
     mutable double* d_virt = nullptr;
     mutable size_t virt_bytes = 0;
 };
@@ -96,17 +86,14 @@ int ensure_device(const ot_tree* t)
     if (ndev <= 0) return OT_E_NODEVICE;
     int dev = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e);
-    const size_t nl = t->host.leaves.size() * sizeof(ot_leaf), ng = t->host.ghost.size() * sizeof(int32_t);
     // one allocation for all tables, each part 256-byte aligned
     const HostTree& h = t->host;
-    constexpr int kParts = 12;
-    const void* part[kParts] = {h.leaves.data(), h.ghost.data(), h.coarse.data(), h.by_level.data(), h.src_slot.data(),
-                                h.src_by_level.data(), h.sched.data(), h.vsrc.data(), h.ghost_v.data(), h.pairs.data(), h.singles.data(), h.vblk.data()};
-    const size_t bytes[kParts] = {nl, ng, h.coarse.size() * sizeof(int32_t), h.by_level.size() * sizeof(int32_t),
-                                  h.src_slot.size() * sizeof(int32_t), h.src_by_level.size() * sizeof(int32_t),
-                                  h.sched.size() * sizeof(int32_t), h.vsrc.size() * sizeof(int32_t),
-                                  h.ghost_v.size() * sizeof(int32_t), h.pairs.size() * sizeof(int32_t), h.singles.size() * sizeof(int32_t),
-                                  h.vblk.size() * sizeof(int32_t)};
+    constexpr int kParts = 9;
+    auto ibytes = [](const std::vector<int32_t>& v) { return v.size() * sizeof(int32_t); };
+    const void* part[kParts] = {h.leaves.data(), h.ghost.data(), h.coarse.data(), h.by_level.data(), h.ghost_v.data(),
+                                h.vblk.data(), h.vlist.data(), h.pairs.data(), h.singles.data()};
+    const size_t bytes[kParts] = {h.leaves.size() * sizeof(ot_leaf), ibytes(h.ghost), ibytes(h.coarse), ibytes(h.by_level),
+                                  ibytes(h.ghost_v), ibytes(h.vblk), ibytes(h.vlist), ibytes(h.pairs), ibytes(h.singles)};
     size_t off[kParts + 1] = {0};
     for (int i = 0; i < kParts; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
     char* base = nullptr;
@@ -117,18 +104,11 @@ int ensure_device(const ot_tree* t)
         (void)hipFree(base);
         return hip_fail(e);
     }
-    t->d_leaves = reinterpret_cast<ot_leaf*>(base + off[0]);
-    t->d_ghost = reinterpret_cast<int32_t*>(base + off[1]);
-    t->d_coarse = reinterpret_cast<int32_t*>(base + off[2]);
-    t->d_by_level = reinterpret_cast<int32_t*>(base + off[3]);
-    t->d_src_slot = reinterpret_cast<int32_t*>(base + off[4]);
-    t->d_src_by_level = reinterpret_cast<int32_t*>(base + off[5]);
-    t->d_sched = reinterpret_cast<int32_t*>(base + off[6]);
-    t->d_vsrc = reinterpret_cast<int32_t*>(base + off[7]);
-    t->d_ghost_v = reinterpret_cast<int32_t*>(base + off[8]);
-    t->d_pairs = reinterpret_cast<int32_t*>(base + off[9]);
-    t->d_singles = reinterpret_cast<int32_t*>(base + off[10]);
-    t->d_vblk = reinterpret_cast<int32_t*>(base + off[11]);
+    auto ints = [&](int i) { return reinterpret_cast<const int32_t*>(base + off[i]); };
+    t->d_base = base;
+    t->dev = DeviceTree{reinterpret_cast<const ot_leaf*>(base + off[0]), ints(1), ints(2), ints(3), static_cast<int64_t>(h.leaves.size()),
+                        ints(4), ints(5), ints(6), h.n_virt,
+                        ints(7), static_cast<int64_t>(h.pairs.size()), ints(8), static_cast<int64_t>(h.singles.size())};
     t->device = dev;
     return resolve_static_workspace(dev);
 }
@@ -165,20 +145,13 @@ int ensure_device(ot_transfer* p)
     return OT_OK;
 }
 
-DeviceTree dev_view(const ot_tree* t)
-{
-    return DeviceTree{t->d_leaves, t->d_ghost, t->d_coarse, t->d_by_level, static_cast<int64_t>(t->host.leaves.size()),
-                      t->d_src_slot, t->d_src_by_level, static_cast<int64_t>(t->host.src_by_level.size()),
-                      t->d_sched, static_cast<int64_t>(t->host.sched.size()), t->d_ghost_v, t->d_vsrc, t->d_vblk, t->host.n_virt,
-                      t->d_pairs, static_cast<int64_t>(t->host.pairs.size()), t->d_singles, static_cast<int64_t>(t->host.singles.size())};
-}
+DeviceTree dev_view(const ot_tree* t) { return t->dev; }
 
 bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }
 
-// bytes of the virtual blocks of one input vector of a kind whose fused kernels read them (the 24-field system)
+// bytes of the virtual blocks of one input vector of a kind
 size_t virtual_bytes(const ot_tree* t, int kind)
 {
-    if (kind != OT_RHS_SYN24) return 0;
     return static_cast<size_t>(ot_rhs_nvar_in(static_cast<ot_rhs_kind>(kind))) * static_cast<size_t>(t->host.n_virt) * 512 * sizeof(double);
 }
 
@@ -248,7 +221,7 @@ int octree_free(ot_tree* tree)
     if (!tree) return OT_OK;
     int rc = OT_OK;
     if (tree->device >= 0) {
-        hipError_t e = hipFree(tree->d_leaves);   // the tables share one allocation
+        hipError_t e = hipFree(tree->d_base);
         if (e != hipSuccess) rc = hip_fail(e);
         if (tree->d_virt && (e = hipFree(tree->d_virt)) != hipSuccess) rc = hip_fail(e);
     }
@@ -290,7 +263,7 @@ int unzip_centred(const ot_tree* tree, int nvar, const double* zipped_dev, doubl
 {
     if (!tree || nvar <= 0 || !zipped_dev || !padded_dev || !aligned8(zipped_dev) || !aligned8(padded_dev)) return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
-    hipError_t e = launch_unzip_centred(dev_view(tree), tree->host.level_start, false, nvar, zipped_dev, padded_dev,
+    hipError_t e = launch_unzip_centred(dev_view(tree), tree->host.level_start, nvar, zipped_dev, padded_dev,
                                         static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
@@ -310,8 +283,8 @@ int rhs_eval(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params,
     if (!tree || !kind_ok(kind) || !params || !padded_dev || !rhs_padded_dev || !aligned8(padded_dev) || !aligned8(rhs_padded_dev))
         return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;
-    RhsArgs a{padded_dev, rhs_padded_dev, nullptr, nullptr, nullptr, nullptr, rhs_padded_dev, 0.0, params->ko_sigma};
-    hipError_t e = launch_rhs(dev_view(tree), kind, false, false, kOutPadded, a, static_cast<hipStream_t>(hip_stream));
+    RhsArgs a{padded_dev, rhs_padded_dev, nullptr, nullptr, nullptr, rhs_padded_dev, 0.0, params->ko_sigma};
+    hipError_t e = launch_rhs(dev_view(tree), kind, false, kOutPadded, a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
@@ -337,8 +310,8 @@ int rhs_eval_zipped(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* 
         hipError_t e = launch_virtual(dv, ot_rhs_nvar_in(kind), zipped_dev, tree->d_virt, s);
         if (e != hipSuccess) return hip_fail(e);
     }
-    RhsArgs a{zipped_dev, rhs_zipped_dev, nullptr, nullptr, nullptr, vbytes ? tree->d_virt : nullptr, rhs_zipped_dev, 0.0, params->ko_sigma};
-    hipError_t e = launch_rhs(dv, kind, true, false, kOutZipped, a, s);
+    RhsArgs a{zipped_dev, rhs_zipped_dev, nullptr, nullptr, vbytes ? tree->d_virt : nullptr, rhs_zipped_dev, 0.0, params->ko_sigma};
+    hipError_t e = launch_rhs(dv, kind, true, kOutZipped, a, s);
     return e == hipSuccess ? OT_OK : hip_fail(e);
 }
 
@@ -364,7 +337,7 @@ static int check_step_buffers(const double* u, size_t u_bytes, const void* ws, s
 
 // the four stage launches of rk_step on tables that are already on the device
 static int rk_step_launch(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u,
-                          void* workspace_dev, size_t need, hipStream_t s)
+                          void* workspace_dev, size_t need, hipStream_t s, bool centred = false)
 {
     const size_t vbytes = virtual_bytes(tree, kind);
     const size_t len = (need - vbytes) / (3 * sizeof(double));
@@ -377,16 +350,18 @@ static int rk_step_launch(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_pa
     // stage vectors ping-pong between sa and sb: a stage reads ghosts of the vector it was given
     // while writing the next one, so the two must be different arrays
     const RhsArgs st[4] = {
-        {u, sa, acc, u, nullptr, virt, sa, 0.5 * dt, sg},    // k1 = F(u):   acc = k1,        sa = u + dt/2 k1
-        {sa, sb, acc, u, nullptr, virt, sb, 0.5 * dt, sg},   // k2 = F(sa):  acc += 2 k2,     sb = u + dt/2 k2
-        {sb, sa, acc, u, nullptr, virt, sa, dt, sg},         // k3 = F(sb):  acc += 2 k3,     sa = u + dt k3
-        {sa, nullptr, acc, u, nullptr, virt, sb, dt / 6.0, sg}};   // k4 = F(sa):  u += dt/6 (acc + k4); sb is free scratch
+        {u, sa, acc, u, virt, sa, 0.5 * dt, sg},    // k1 = F(u):   acc = k1,        sa = u + dt/2 k1
+        {sa, sb, acc, u, virt, sb, 0.5 * dt, sg},   // k2 = F(sa):  acc += 2 k2,     sb = u + dt/2 k2
+        {sb, sa, acc, u, virt, sa, dt, sg},         // k3 = F(sb):  acc += 2 k3,     sa = u + dt k3
+        {sa, nullptr, acc, u, virt, sb, dt / 6.0, sg}};   // k4 = F(sa):  u += dt/6 (acc + k4); sb is free scratch
     const Epilogue ep[4] = {kRkFirst, kRkMiddle, kRkMiddle, kRkLast};
     for (int i = 0; i < 4; ++i) {
         // the virtual blocks of this stage's input first; the stream orders them before the stage kernel and
         // after the previous stage's reads of the same array
-        hipError_t e = vbytes ? launch_virtual(dv, ot_rhs_nvar_in(kind), st[i].in, virt, s) : hipSuccess;
-        if (e == hipSuccess) e = launch_rhs(dv, kind, true, false, ep[i], st[i], s);
+        hipError_t e = hipSuccess;
+        if (vbytes && centred) e = launch_virtual_centred(dv, tree->host.vlevel_start, ot_rhs_nvar_in(kind), st[i].in, virt, s);
+        else if (vbytes) e = launch_virtual(dv, ot_rhs_nvar_in(kind), st[i].in, virt, s);
+        if (e == hipSuccess) e = launch_rhs(dv, kind, true, ep[i], st[i], s);
         if (e != hipSuccess) return hip_fail(e);
     }
     return OT_OK;
@@ -421,47 +396,18 @@ int rk_step_static(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* p
 
 int rk_centred_workspace_bytes(const ot_tree* tree, ot_rhs_kind kind, size_t* bytes)
 {
-    size_t zipped3 = 0;
-    if (int rc = rk_workspace_bytes(tree, kind, &zipped3)) return rc;
-    zipped3 -= virtual_bytes(tree, kind);
-    // three zipped vectors, then the padded blocks of the source leaves of the current stage vector
-    *bytes = zipped3 + static_cast<size_t>(ot_rhs_nvar_in(kind)) * tree->host.src_by_level.size() * 2744 * sizeof(double);
-    return OT_OK;
+    return rk_workspace_bytes(tree, kind, bytes);   // the two ghost rules fill the same virtual blocks
 }
 
 int rk_step_centred(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* params, double dt, double* u_zipped_dev,
                     void* workspace_dev, size_t workspace_bytes, void* hip_stream)
 {
     if (!tree || !kind_ok(kind) || !params || !u_zipped_dev || !workspace_dev) return OT_E_BADARG;
-    size_t need = 0, zipped3 = 0;
-    if (int rc = rk_centred_workspace_bytes(tree, kind, &need)) return rc;
-    if (int rc = rk_workspace_bytes(tree, kind, &zipped3)) return rc;
-    zipped3 -= virtual_bytes(tree, kind);
-    if (int rc = check_step_buffers(u_zipped_dev, zipped3 / 3, workspace_dev, workspace_bytes, need)) return rc;
+    size_t need = 0;
+    if (int rc = rk_workspace_bytes(tree, kind, &need)) return rc;
+    if (int rc = check_step_buffers(u_zipped_dev, (need - virtual_bytes(tree, kind)) / 3, workspace_dev, workspace_bytes, need)) return rc;
     if (int rc = ensure_device(tree)) return rc;
-    const size_t len = zipped3 / (3 * sizeof(double));
-    const int nvar = ot_rhs_nvar_in(kind);
-    double* acc = static_cast<double*>(workspace_dev);
-    double* sa = acc + len;
-    double* sb = sa + len;
-    double* pad = sb + len;                     // padded source leaves of the current stage vector
-    double* u = u_zipped_dev;
-    const DeviceTree dv = dev_view(tree);
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const double sg = params->ko_sigma;
-    // per stage: the few leaves that serve as coarser sources are ghost-filled level by level into
-    // `pad`; the fused stage kernel then reads everything else straight from the zipped vector
-    const RhsArgs st[4] = {{u, sa, acc, u, pad, nullptr, sa, 0.5 * dt, sg},
-                           {sa, sb, acc, u, pad, nullptr, sb, 0.5 * dt, sg},
-                           {sb, sa, acc, u, pad, nullptr, sa, dt, sg},
-                           {sa, nullptr, acc, u, pad, nullptr, sb, dt / 6.0, sg}};
-    const Epilogue ep[4] = {kRkFirst, kRkMiddle, kRkMiddle, kRkLast};
-    for (int i = 0; i < 4; ++i) {
-        hipError_t e = launch_unzip_centred(dv, tree->host.src_level_start, true, nvar, st[i].in, pad, s);
-        if (e == hipSuccess) e = launch_rhs(dv, kind, true, true, ep[i], st[i], s);
-        if (e != hipSuccess) return hip_fail(e);
-    }
-    return OT_OK;
+    return rk_step_launch(tree, kind, params, dt, u_zipped_dev, workspace_dev, need, static_cast<hipStream_t>(hip_stream), true);
 }
 
 int regrid_plan(const ot_tree* from, const ot_tree* to, ot_transfer** out)

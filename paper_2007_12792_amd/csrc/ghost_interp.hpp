@@ -1,6 +1,6 @@
-// Ghost values that come from a coarser leaf: separable six-point interpolation staged in LDS, for
-// whole boxes and for face slabs, with the clamped and the centred stencil rule; and the two halves
-// of a tile fill (request from memory, commit to LDS).  Private to kernels.hip.
+// Ghost values that come from a coarser leaf, for the kernels that write padded blocks (unzip, unzip_centred):
+// separable six-point interpolation of whole boxes staged in LDS, with the clamped and the centred stencil
+// rule; and the two halves of a tile fill (request from memory, store to LDS).  Private to kernels.hip.
 #pragma once
 #include "tile.hpp"
 
@@ -207,17 +207,14 @@ struct CentredBox {
     }
 };
 
-// every coarser source leaf of the block, one after the other; pbase = one variable's compact array of
-// padded source leaves (or, with by_id, the padded array of all blocks)
-template <bool BY_ID = false>
+// every coarser source leaf of the block, one after the other; pbase = one variable's padded array of all blocks
 __device__ __forceinline__ void interp_boxes_centred(double* tile, double* scratch, const BlockInfo& bi,
                                                      const double* __restrict__ pbase, int tid)
 {
     const BoxPlan& bp = bi.box;
     const int ns = bp.rbeg[bp.nround];
     auto box = [&](CentredBox& cb, int s) {
-        const int64_t src = BY_ID ? bi.cs[2 * s] : bi.slot[s];
-        cb.set(bi, pbase + src * PBLK, bp.sx[s], bp.nx[s], bp.sy[s], bp.ny[s], bp.sz[s], bp.nz[s]);
+        cb.set(bi, pbase + (int64_t)bi.cs[2 * s] * PBLK, bp.sx[s], bp.nx[s], bp.sy[s], bp.ny[s], bp.sz[s], bp.nz[s]);
     };
     if (ns == 0) return;
     CentredBox cur, nxt;
@@ -232,36 +229,11 @@ __device__ __forceinline__ void interp_boxes_centred(double* tile, double* scrat
         cur = nxt;
     }
 }
-// the same where only the face slabs of the tile are read: one 3 x 8 x 8 box per coarser face
-__device__ __forceinline__ void interp_faces_centred(double* tile, double* scratch, const BlockInfo& bi,
-                                                     const double* __restrict__ pbase, int tid)
-{
-    const int n = bi.cs[16];
-    auto box = [&](CentredBox& cb, int q) {
-        const int face = bi.cs[17 + 2 * q], ax = face >> 1, s0 = (face & 1) ? PAD + NPT : 0;
-        cb.set(bi, pbase + (int64_t)bi.slot[bi.box.face_src[q]] * PBLK, ax == 0 ? s0 : PAD, ax == 0 ? PAD : NPT,
-               ax == 1 ? s0 : PAD, ax == 1 ? PAD : NPT, ax == 2 ? s0 : PAD, ax == 2 ? PAD : NPT);
-    };
-    if (n == 0) return;
-    CentredBox cur, nxt;
-    double c[2];
-    box(cur, 0);
-    cur.request(c, tid);
-#pragma unroll 1
-    for (int q = 0; q < n; ++q) {
-        cur.stage(scratch, c, tid);
-        if (q + 1 < n) { box(nxt, q + 1); nxt.request(c, tid); }
-        cur.sweep(tile, scratch, bi, tid);
-        cur = nxt;
-    }
-}
-
 // Filling the tile of one variable is split in two so that the global loads of the next variable
 // can be in flight while the current one is being differentiated:
-//   prefetch(): issue the planned loads into registers;
-//   commit():   store them into a tile buffer, then (zipped input only) interpolate what comes from
-//               coarser leaves.  `base` is that variable's zipped array (ZIN) or this block's padded
-//               data.  All threads call both.  commit() does NOT end with a barrier.
+//   prefetch():   issue the planned loads into registers;
+//   store_tile(): store them into a tile buffer.
+// `base` is that variable's zipped array or this block's padded data.  All threads call both.
 // USE = how many plan entries per thread are in use (PLAN_FACE: faces only).
 // VIRT: plan entries with bit 0 set are offsets into vbase, that variable's virtual blocks.
 template <int NPLAN, int USE, bool VIRT = false, bool REG>
@@ -280,79 +252,15 @@ __device__ __forceinline__ void prefetch(double (&v)[NPLAN], const FillPlan<NPLA
     }
 }
 
-// Values of the coarser face neighbours can be requested together with the tile data
-// (coarse_prefetch) so that their latency hides behind the stencil work: CPRE slots, in the order of
-// the block's coarse-face list; further faces are loaded late.
-constexpr int CPRE = 3;
-__device__ __forceinline__ void coarse_prefetch(double (&cv)[CPRE], const BlockInfo& bi, const double* __restrict__ base, int tid)
-{
-    const int n = bi.cs[16];
-#pragma unroll
-    for (int q = 0; q < CPRE; ++q)
-        if (q < n) cv[q] = ldg(base, ((uint32_t)bi.cs[18 + 2 * q] * BLK + tid) * 8u);
-}
-
-// CENTRED: ghost values from coarser leaves follow the centred rule and come from pbase (that
-// variable's padded source leaves).
-// INTERP = false: the caller knows that the block has no coarser source (the interpolation is compiled out).
-template <bool ZIN, int NPLAN, int USE, bool CENTRED = false, bool INTERP = true, bool REG>
-__device__ __forceinline__ void commit(double* tile, double* scratch, const BlockInfo& bi, const FillPlan<NPLAN, REG>& fp,
-                                       const double (&v)[NPLAN], const double (&cv)[CPRE], bool have_cv,
-                                       const double* __restrict__ base, int tid, const double* __restrict__ pbase = nullptr)
+// the requested values into a tile buffer; does NOT end with a barrier
+template <int NPLAN, int USE, bool REG>
+__device__ __forceinline__ void store_tile(double* tile, const FillPlan<NPLAN, REG>& fp, const double (&v)[NPLAN], int tid)
 {
 #pragma unroll
     for (int m = 0; m < USE; ++m) {
         int d = fp.dst(m);
         if (USE == PLAN_FACE && NPLAN > PLAN_FACE && m == USE - 1 && tid + m * NTHREADS >= NFACE) d = DUMMY;
         tile[d] = v[m];
-    }
-    if (!ZIN || !INTERP || bi.cs[0] < 0) return;
-    // Control flow below is uniform over the workgroup.
-    if (CENTRED) {
-        if (USE == PLAN_FACE) interp_faces_centred(tile, scratch, bi, pbase, tid);
-        else interp_boxes_centred(tile, scratch, bi, pbase, tid);
-    } else if (USE == PLAN_FACE) {
-        // Faces only: each face neighbour that is coarser supplies a 3 x 8 x 8 slab.  Wavefront w
-        // owns the coarse plane cz = w: it interpolates that plane in x and then in y out of its
-        // own staging area with no workgroup barrier; only the z pass, which combines the planes,
-        // needs one.  The y-pass results are double-buffered across faces.
-        const int n = bi.cs[16];
-        const int wave = tid >> 6, lane = tid & 63;
-        double* Cs = scratch + wave * 128;       // this wavefront's coarse plane, [cy][cx]
-        double* T1s = Cs + 64;                   // after the x pass, [cy][tx]
-        __syncthreads();                         // the staging arrays may still be read as wy / wz
-#pragma unroll 1
-        for (int q = 0; q < n; ++q) {
-            const int face = bi.cs[17 + 2 * q], ax = face >> 1, s0 = (face & 1) ? PAD + NPT : 0;
-            const int sx = ax == 0 ? s0 : PAD, sy = ax == 1 ? s0 : PAD, sz = ax == 2 ? s0 : PAD;
-            const int nx = ax == 0 ? PAD : NPT, ny = ax == 1 ? PAD : NPT, nz = ax == 2 ? PAD : NPT;
-            const uint32_t mx = div_magic(nx), mxy = div_magic(nx * ny);
-            const int fx0 = (NPT * bi.ax + sx + 16 - PAD) & 15;
-            const int fy0 = (NPT * bi.ay + sy + 16 - PAD) & 15;
-            const int fz0 = (NPT * bi.az + sz + 16 - PAD) & 15;
-            double* T2 = scratch + 1024 + (q & 1) * 512;   // after the y pass, [cz][ty][tx], 64 per plane
-            double cval;
-            if (have_cv && q < CPRE) cval = q == 0 ? cv[0] : (q == 1 ? cv[1] : cv[2]);
-            else cval = ldg(base, ((uint32_t)bi.cs[18 + 2 * q] * BLK + tid) * 8u);
-            Cs[lane] = cval;
-            __builtin_amdgcn_wave_barrier();
-            if (lane < NPT * nx) {                                   // x pass, item (cy, tx)
-                const int cy = div_by(lane, mx), tx = lane - cy * nx;
-                T1s[cy * NPT + tx] = interp_line(&Cs[cy * NPT], 1, fx0 + tx, bi.lag);
-            }
-            __builtin_amdgcn_wave_barrier();
-            if (lane < ny * nx) {                                    // y pass, item (ty, tx)
-                const int ty = div_by(lane, mx), tx = lane - ty * nx;
-                T2[wave * 64 + lane] = interp_line(&T1s[tx], NPT, fy0 + ty, bi.lag);
-            }
-            __syncthreads();
-            if (tid < nz * ny * nx) {                                // z pass, into the tile
-                const int tz = div_by(tid, mxy), r = tid - tz * nx * ny, ty = div_by(r, mx), tx = r - ty * nx;
-                tile[tidx(sz + tz, sy + ty, sx + tx)] = interp_line(&T2[r], 64, fz0 + tz, bi.lag);
-            }
-        }
-    } else {
-        interp_boxes(tile, scratch, bi, base, tid);
     }
 }
 

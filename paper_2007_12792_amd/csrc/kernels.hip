@@ -27,14 +27,11 @@ namespace {
 // ---------------------------------------------------------------- right-hand-side kernel
 
 // LDS of the right-hand-side kernels (in doubles / words)
-template <int KIND, bool ZIN>
+template <int KIND>
 struct RhsLds {
     static constexpr int NBUF = KIND == OT_RHS_SYN24 ? 2 : 1;
-    // SYN24 keeps wy / wz in `scratch` and stages whole boxes of coarser leaves there; the other kinds read face
-    // slabs only, whose interpolation needs 2,048 doubles
-    static constexpr int FACE_STAGING = 1024 + 2 * 512;
-    static_assert(FACE_STAGING >= 810, "centred interpolation of one 3 x 8 x 8 face slab");
-    static constexpr int NSCRATCH = KIND == OT_RHS_SYN24 ? SCRATCH : (ZIN ? FACE_STAGING : 1);
+    // the 24-field system keeps D1_z u and D1_y u of the variable in hand here (mixed derivatives)
+    static constexpr int NW = KIND == OT_RHS_SYN24 ? WZ + WY : 1;
     // second derivatives (SYN24 only) read the edge slabs of the tile too
     static constexpr int NPLAN = KIND == OT_RHS_SYN24 ? PLAN_EDGE : PLAN_FACE;
     static constexpr int NPOINTS = KIND == OT_RHS_SYN24 ? NEDGE : NFACE;
@@ -43,212 +40,184 @@ struct RhsLds {
 };
 
 // The right-hand side (and Runge-Kutta stage update) of whole blocks, one block per workgroup, all its variables.
-// SCHED = false: block = position of the workgroup.  SCHED = true (24-field system): the workgroup takes its block
-// from the tree's schedule (see HostTree::sched), in which chunks of blocks without a coarser source are dealt in
-// among chunks of blocks with one; the former run the body compiled with COARSE = false: no box plan, no
-// interpolation code (2 spilled registers instead of 11, and 5 % less time on a uniform tree).
-// The body is a generic lambda inside the kernel, so that it names the LDS arrays directly in both instances.
-template <int KIND, bool ZIN, int EPI, bool CENTRED = false, bool SCHED = false>
-__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND, CENTRED)) void k_rhs(DeviceTree tr, RhsArgs a)
+// Zipped input (ZIN): the tile is filled through the ghost table in which coarser neighbours appear as virtual
+// blocks, which k_virtual or k_virtual_centred has filled before the launch, so every tile entry is a copy or an
+// injection and no interpolation happens here; the two ghost rules differ only in which of the two kernels ran.
+// LIST: the workgroup takes its block from the list of blocks that are not part of a sibling pair (24-field system,
+// whose pairs run k_rhs_pair); otherwise block = position of the workgroup.
+template <int KIND, bool ZIN, int EPI, bool LIST = false>
+__global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTree tr, RhsArgs a)
 {
-    static_assert(ZIN || !CENTRED, "the centred ghost rule applies to zipped input");
-    static_assert(ZIN || !SCHED, "the schedule is for zipped input");
-    using L = RhsLds<KIND, ZIN>;
-    // the 24-field kernel on zipped input reads what comes from coarser leaves out of virtual blocks, filled by
-    // k_virtual before the launch: every block then runs the path without interpolation
-    constexpr bool VIRT = ZIN && !CENTRED && KIND == OT_RHS_SYN24;
+    using L = RhsLds<KIND>;
     __shared__ double tiles[L::NBUF * TILE];
-    __shared__ double scratch[L::NSCRATCH];
+    __shared__ double wyz[L::NW];
     __shared__ BlockInfo bi;
     __shared__ uint32_t plan_src[L::NPLAN_SRC];
     constexpr int NPLAN = L::NPLAN, NPOINTS = L::NPOINTS;
     constexpr bool PLAN_IN_REGS = L::PLAN_IN_REGS;
 
-    auto block = [&](const int64_t b, auto coarse_tag) {
-        constexpr bool COARSE = decltype(coarse_tag)::value;
-        constexpr bool CEN = CENTRED && COARSE;      // the ghost rules differ only where a coarser source exists
+    const int64_t q = block_of_workgroup(blockIdx.x);
+    if (q >= (LIST ? tr.n_singles : tr.nb)) return;  // uniform over the workgroup, like everything below
+    const int64_t b = LIST ? (int64_t)tr.singles[q] : q;
 
-        const int tid = threadIdx.x;
-        const int64_t nb = tr.nb;
-        load_block_info<VIRT>(bi, tr, b, tid);
+    const int tid = threadIdx.x;
+    const int64_t nb = tr.nb;
+    load_block_info<ZIN>(bi, tr, b, tid);
+    __syncthreads();
+
+    int i, j, k;
+    point_of(tid, i, j, k);
+    const int c = tidx(k + PAD, j + PAD, i + PAD);
+    // byte offsets of this thread's point inside one variable's zipped array / inside a padded block
+    const uint32_t o8 = ((uint32_t)b * BLK + (k * NPT + j) * NPT + i) * 8u;
+    const uint32_t p8 = (((k + PAD) * NP + (j + PAD)) * NP + (i + PAD)) * 8u;
+    // 1/h = 2^(l+3) and 1/h^2, built from the level as bit patterns in scalar registers (the level is the same
+    // for the whole workgroup, which the compiler cannot see through the LDS copy)
+    const int lvl = __builtin_amdgcn_readfirstlane((int)bi.level);
+    const double ih = __longlong_as_double((long long)(1026 + lvl) << 52), ih2 = __longlong_as_double((long long)(1029 + 2 * lvl) << 52);
+    const double sigma = a.sigma;
+
+    FillPlan<NPLAN, PLAN_IN_REGS> fp;
+    fp.src = plan_src;
+    if (ZIN) make_plan_zipped<NPLAN, NPOINTS>(fp, bi, tid);
+    else make_plan_padded<NPLAN, NPOINTS>(fp, tid);
+    double pv[NPLAN];
+
+    auto var_base = [&](int v) -> const double* {
+        return ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK;
+    };
+    auto virt_base = [&](int v) -> const double* {  // variable v's virtual blocks
+        return ZIN ? a.virt + (int64_t)v * tr.n_virt * BLK : nullptr;
+    };
+    auto stage = [&](int v) {   // bring variable v into tile buffer 0 (barrier before and after)
         __syncthreads();
-        if (tid == 0 && COARSE && (KIND == OT_RHS_SYN24 || CEN)) make_box_plan(bi, false);   // read only after the next barrier
-
-        int i, j, k;
-        point_of(tid, i, j, k);
-        const int c = tidx(k + PAD, j + PAD, i + PAD);
-        // byte offsets of this thread's point inside one variable's zipped array / inside a padded block
-        const uint32_t o8 = ((uint32_t)b * BLK + (k * NPT + j) * NPT + i) * 8u;
-        const uint32_t p8 = (((k + PAD) * NP + (j + PAD)) * NP + (i + PAD)) * 8u;
-        // 1/h = 2^(l+3) and 1/h^2, built from the level as bit patterns in scalar registers (the level is the same
-        // for the whole workgroup, which the compiler cannot see through the LDS copy)
-        const int lvl = __builtin_amdgcn_readfirstlane((int)bi.level);
-        const double ih = __longlong_as_double((long long)(1026 + lvl) << 52), ih2 = __longlong_as_double((long long)(1029 + 2 * lvl) << 52);
-        const double sigma = a.sigma;
-
-        FillPlan<NPLAN, PLAN_IN_REGS> fp;
-        fp.src = plan_src;
-        if (ZIN) make_plan_zipped<NPLAN, NPOINTS>(fp, bi, tid);
-        else make_plan_padded<NPLAN, NPOINTS>(fp, tid);
-        double pv[NPLAN];
-        double cv[CPRE];   // values of coarser face neighbours requested ahead (SYN24 first-derivative passes)
-
-        auto var_base = [&](int v) -> const double* {
-            return ZIN ? a.in + (int64_t)v * nb * BLK : a.in + ((int64_t)v * nb + b) * PBLK;
-        };
-        auto virt_base = [&](int v) -> const double* {  // variable v's virtual blocks
-            return VIRT ? a.virt + (int64_t)v * tr.n_virt * BLK : nullptr;
-        };
-        auto pad_base = [&](int v) -> const double* {   // centred rule: variable v's padded source leaves
-            return CEN ? a.pad_src + (int64_t)v * tr.n_src * PBLK : nullptr;
-        };
-        auto stage = [&](int v) {   // bring variable v into tile buffer 0 (barrier before and after)
-            __syncthreads();
-            prefetch<NPLAN, PLAN_FACE, VIRT>(pv, fp, var_base(v), tid, virt_base(v));
-            commit<ZIN, NPLAN, PLAN_FACE, CEN, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(v), tid, pad_base(v));
-            __syncthreads();
-        };
-        auto centre = [&](int v) -> double {   // this thread's own value of variable v
-            return ZIN ? ldg(a.in + (int64_t)v * nb * BLK, o8) : ldg(a.in + ((int64_t)v * nb + b) * PBLK, p8);
-        };
-
-        if (KIND == OT_RHS_DERIVS) {
-            stage(0);
-            const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
-            const EpiOperands e2 = epi_prefetch<EPI>(a, nb, 2, o8), e3 = epi_prefetch<EPI>(a, nb, 3, o8);
-            const PointOps p = point_ops<true>(tiles, c, 0.0, ih, ih2);
-            emit<EPI>(a, nb, 0, b, o8, p8, p.dx, e0);
-            emit<EPI>(a, nb, 1, b, o8, p8, p.dy, e1);
-            emit<EPI>(a, nb, 2, b, o8, p8, p.dz, e2);
-            emit<EPI>(a, nb, 3, b, o8, p8, p.lap, e3);
-        } else if (KIND == OT_RHS_WAVE) {
-            stage(0);
-            prefetch<NPLAN, PLAN_FACE, VIRT>(pv, fp, var_base(1), tid, virt_base(1));   // pi is on its way while u is differentiated
-            const PointOps pu = point_ops<true>(tiles, c, sigma, ih, ih2);
-            // the operands of the stage update are requested only now: four more values live during the stencils
-            // above push the kernel over the 64 registers that let four workgroups share a compute unit, and a
-            // kernel that spills there loses a quarter of its speed (the fence keeps the scheduler from moving the
-            // loads back up)
-            __syncthreads();
-            commit<ZIN, NPLAN, PLAN_FACE, CEN, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(1), tid, pad_base(1));
-            __builtin_amdgcn_sched_barrier(0);
-            const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
-            __syncthreads();
-            const PointOps pp = point_ops<false>(tiles, c, sigma, ih, ih2);
-            emit<EPI>(a, nb, 0, b, o8, p8, pp.u0 + pu.ko, e0);
-            emit<EPI>(a, nb, 1, b, o8, p8, pu.lap + pp.ko, e1);
-        } else if (KIND == OT_RHS_BURGERS) {
-            stage(0);
-            const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8);
-            const PointOps p = point_ops<false>(tiles, c, sigma, ih, ih2);
-            const double flux = p.u0 * p.dx;
-            emit<EPI>(a, nb, 0, b, o8, p8, p.ko - flux, e0);
-        } else {
-            // SYN24.  The variables are streamed in descending cyclic order (see syn24_stream).  The
-            // first ten real passes (variables 9..0) evaluate the second-derivative combinations Lap_s;
-            // each thread parks them at its own point in variables 10+s of the `stash` array, from where
-            // the later passes (variables 23..10, which need Lap_{a mod 10}) read them back before those
-            // slots receive their final values.  Per-thread state thus shrinks to one gradient.
-            //
-            // The tile is double-buffered and global memory is requested ahead of its use: tile data
-            // of the next variable is loaded into registers at the top of a pass and committed to the
-            // other LDS buffer at its end (one barrier per pass, plus the one inside mixed_derivs); the
-            // pointwise operands of the next pass (RK accumulator and state, u_{a+11}, Lap) likewise.
-            double* wz = scratch;
-            double* wy = scratch + WZ;
-            const double halpha = 0.5 * centre(0), bx = centre(1), by = centre(2), bz = centre(3);
-            const double Gxx = 1.0 - 0.125 * centre(4), Gxy = -(0.125 * centre(5)), Gxz = -(0.125 * centre(6));
-            const double Gyy = 1.0 - 0.125 * centre(7), Gyz = -(0.125 * centre(8)), Gzz = 1.0 - 0.125 * centre(9);
-            double nx = 0, ny = 0, nz = 0;
-            const int ownz = k * PS + (j + PAD) * RS + (i + PAD), owny = k * YPS + j * RS + (i + PAD);
-            struct Look { double unext, lap; EpiOperands eo; };
-
-            auto stash_base = [&](int v) -> double* {   // where Lap_{v-10} is parked (v = 10..19)
-                return EPI == kOutPadded ? a.stash + ((int64_t)v * nb + b) * PBLK : a.stash + (int64_t)v * nb * BLK;
-            };
-            const uint32_t s8 = EPI == kOutPadded ? p8 : o8;
-
-            // top of pass t: request the tile data of pass t+1 and this pass's own pointwise operands.
-            // NEXT_USE says how much of the tile pass t+1 reads (edges only if it takes second derivatives).
-            auto issue = [&](int t, int f, Look& l, int& f1, auto next_use) {
-                constexpr int NEXT_USE = decltype(next_use)::value;
-                if (t + 1 < NSTREAM) {
-                    f1 = syn24_stream(t + 1);
-                    prefetch<NPLAN, NEXT_USE, VIRT>(pv, fp, var_base(f1), tid, virt_base(f1));
-                    if (ZIN && COARSE && !CEN && NEXT_USE == PLAN_FACE) coarse_prefetch(cv, bi, var_base(f1), tid);
-                }
-                l.unext = centre((f + 11) % 24);
-                l.eo = epi_prefetch<EPI>(a, nb, f, o8);
-                if (t > 10) l.lap = ldg(stash_base(10 + f % 10), s8);
-            };
-            using UseEdge = std::integral_constant<int, PLAN_EDGE>;
-            using UseFace = std::integral_constant<int, PLAN_FACE>;
-            // pass over a variable with second derivatives (9..0)
-            auto pass_d2 = [&](int t, auto next_use) {
-                constexpr int NEXT_USE = decltype(next_use)::value;
-                const double* T = tiles + (t & 1) * TILE;
-                const int f = syn24_stream(t);
-                int f1 = 0;
-                Look l{0.0, 0.0, {0.0, 0.0}};
-                issue(t, f, l, f1, next_use);
-                const Syn24Part p = syn24_axes<true>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
-                const Mixed mx = mixed_derivs(T, wy, wz, tid, owny, ownz, ih);
-                double off = Gxy * mx.dxy;
-                off = fma(Gxz, mx.dxz, off);
-                off = fma(Gyz, mx.dyz, off);
-                const double lap = fma(2.0, off, p.diag);
-                stg(stash_base(10 + f), s8, lap);
-                emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l.unext), l.eo);
-                commit<ZIN, NPLAN, NEXT_USE, CEN, COARSE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, NEXT_USE == PLAN_FACE, var_base(f1), tid, pad_base(f1));
-                __syncthreads();
-            };
-            // pass over a variable without second derivatives (23..10)
-            auto pass_light = [&](int t) {
-                const double* T = tiles + (t & 1) * TILE;
-                const int f = syn24_stream(t);
-                int f1 = 0;
-                Look l{0.0, 0.0, {0.0, 0.0}};
-                issue(t, f, l, f1, UseFace{});
-                const Syn24Part p = syn24_axes<false>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
-                emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, l.lap, halpha, l.unext), l.eo);
-                if (t + 1 < NSTREAM) {
-                    commit<ZIN, NPLAN, PLAN_FACE, CEN, COARSE>(tiles + ((t + 1) & 1) * TILE, scratch, bi, fp, pv, cv, true, var_base(f1), tid, pad_base(f1));
-                    __syncthreads();
-                }
-            };
-
-            {   // pass 0: gradient of variable 10 only
-                const int f = syn24_stream(0), f1 = syn24_stream(1);
-                prefetch<NPLAN, PLAN_FACE, VIRT>(pv, fp, var_base(f), tid, virt_base(f));
-                if (CEN) __syncthreads();            // the box plan, made by one thread, is read in this commit already
-                commit<ZIN, NPLAN, PLAN_FACE, CEN, COARSE>(tiles, scratch, bi, fp, pv, cv, false, var_base(f), tid, pad_base(f));
-                __syncthreads();
-                prefetch<NPLAN, PLAN_EDGE, VIRT>(pv, fp, var_base(f1), tid, virt_base(f1));
-                nx = d1_at(tiles, c, 1, ih); ny = d1_at(tiles, c, RS, ih); nz = d1_at(tiles, c, PS, ih);
-                commit<ZIN, NPLAN, PLAN_EDGE, CEN, COARSE>(tiles + TILE, scratch, bi, fp, pv, cv, false, var_base(f1), tid, pad_base(f1));
-                __syncthreads();
-            }
-    #pragma unroll 1
-            for (int t = 1; t < 10; ++t) pass_d2(t, UseEdge{});
-            pass_d2(10, UseFace{});
-    #pragma unroll 1
-            for (int t = 11; t < NSTREAM; ++t) pass_light(t);
-        }
+        prefetch<NPLAN, PLAN_FACE, ZIN>(pv, fp, var_base(v), tid, virt_base(v));
+        store_tile<NPLAN, PLAN_FACE>(tiles, fp, pv, tid);
+        __syncthreads();
+    };
+    auto centre = [&](int v) -> double {   // this thread's own value of variable v
+        return ZIN ? ldg(a.in + (int64_t)v * nb * BLK, o8) : ldg(a.in + ((int64_t)v * nb + b) * PBLK, p8);
     };
 
-    const int64_t q = block_of_workgroup(blockIdx.x);
-    if constexpr (!SCHED) {
-        if (q >= tr.nb) return;                      // uniform over the workgroup, like everything below
-        block(q, std::integral_constant<bool, !VIRT>{});
-    } else if constexpr (VIRT) {                     // the blocks that are not part of a sibling pair
-        if (q >= tr.n_singles) return;
-        block(tr.singles[q], std::false_type{});
+    if (KIND == OT_RHS_DERIVS) {
+        stage(0);
+        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
+        const EpiOperands e2 = epi_prefetch<EPI>(a, nb, 2, o8), e3 = epi_prefetch<EPI>(a, nb, 3, o8);
+        const PointOps p = point_ops<true>(tiles, c, 0.0, ih, ih2);
+        emit<EPI>(a, nb, 0, b, o8, p8, p.dx, e0);
+        emit<EPI>(a, nb, 1, b, o8, p8, p.dy, e1);
+        emit<EPI>(a, nb, 2, b, o8, p8, p.dz, e2);
+        emit<EPI>(a, nb, 3, b, o8, p8, p.lap, e3);
+    } else if (KIND == OT_RHS_WAVE) {
+        stage(0);
+        prefetch<NPLAN, PLAN_FACE, ZIN>(pv, fp, var_base(1), tid, virt_base(1));   // pi is on its way while u is differentiated
+        const PointOps pu = point_ops<true>(tiles, c, sigma, ih, ih2);
+        // the operands of the stage update are requested only now: four more values live during the stencils
+        // above push the kernel over the 64 registers that let four workgroups share a compute unit, and a
+        // kernel that spills there loses a quarter of its speed (the fence keeps the scheduler from moving the
+        // loads back up)
+        __syncthreads();
+        store_tile<NPLAN, PLAN_FACE>(tiles, fp, pv, tid);
+        __builtin_amdgcn_sched_barrier(0);
+        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
+        __syncthreads();
+        const PointOps pp = point_ops<false>(tiles, c, sigma, ih, ih2);
+        emit<EPI>(a, nb, 0, b, o8, p8, pp.u0 + pu.ko, e0);
+        emit<EPI>(a, nb, 1, b, o8, p8, pu.lap + pp.ko, e1);
+    } else if (KIND == OT_RHS_BURGERS) {
+        stage(0);
+        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8);
+        const PointOps p = point_ops<false>(tiles, c, sigma, ih, ih2);
+        const double flux = p.u0 * p.dx;
+        emit<EPI>(a, nb, 0, b, o8, p8, p.ko - flux, e0);
     } else {
-        if (q >= tr.n_sched) return;
-        const int32_t e = tr.sched[q];
-        if (e < 0) return;                           // padding of a unit
-        if (e & kSchedCoarse) block(e & ~kSchedCoarse, std::true_type{});
-        else block(e, std::false_type{});
+        // SYN24.  The variables are streamed in descending cyclic order (see syn24_stream).  The
+        // first ten real passes (variables 9..0) evaluate the second-derivative combinations Lap_s;
+        // each thread parks them at its own point in variables 10+s of the `stash` array, from where
+        // the later passes (variables 23..10, which need Lap_{a mod 10}) read them back before those
+        // slots receive their final values.  Per-thread state thus shrinks to one gradient.
+        //
+        // The tile is double-buffered and global memory is requested ahead of its use: tile data
+        // of the next variable is loaded into registers at the top of a pass and stored to the
+        // other LDS buffer at its end (one barrier per pass, plus the one inside mixed_derivs); the
+        // pointwise operands of the next pass (RK accumulator and state, u_{a+11}, Lap) likewise.
+        double* wz = wyz;
+        double* wy = wyz + WZ;
+        const double halpha = 0.5 * centre(0), bx = centre(1), by = centre(2), bz = centre(3);
+        const double Gxx = 1.0 - 0.125 * centre(4), Gxy = -(0.125 * centre(5)), Gxz = -(0.125 * centre(6));
+        const double Gyy = 1.0 - 0.125 * centre(7), Gyz = -(0.125 * centre(8)), Gzz = 1.0 - 0.125 * centre(9);
+        double nx = 0, ny = 0, nz = 0;
+        const int ownz = k * PS + (j + PAD) * RS + (i + PAD), owny = k * YPS + j * RS + (i + PAD);
+        struct Look { double unext, lap; EpiOperands eo; };
+
+        auto stash_base = [&](int v) -> double* {   // where Lap_{v-10} is parked (v = 10..19)
+            return EPI == kOutPadded ? a.stash + ((int64_t)v * nb + b) * PBLK : a.stash + (int64_t)v * nb * BLK;
+        };
+        const uint32_t s8 = EPI == kOutPadded ? p8 : o8;
+
+        // top of pass t: request the tile data of pass t+1 and this pass's own pointwise operands.
+        // NEXT_USE says how much of the tile pass t+1 reads (edges only if it takes second derivatives).
+        auto issue = [&](int t, int f, Look& l, int& f1, auto next_use) {
+            constexpr int NEXT_USE = decltype(next_use)::value;
+            if (t + 1 < NSTREAM) {
+                f1 = syn24_stream(t + 1);
+                prefetch<NPLAN, NEXT_USE, ZIN>(pv, fp, var_base(f1), tid, virt_base(f1));
+            }
+            l.unext = centre((f + 11) % 24);
+            l.eo = epi_prefetch<EPI>(a, nb, f, o8);
+            if (t > 10) l.lap = ldg(stash_base(10 + f % 10), s8);
+        };
+        using UseEdge = std::integral_constant<int, PLAN_EDGE>;
+        using UseFace = std::integral_constant<int, PLAN_FACE>;
+        // pass over a variable with second derivatives (9..0)
+        auto pass_d2 = [&](int t, auto next_use) {
+            constexpr int NEXT_USE = decltype(next_use)::value;
+            const double* T = tiles + (t & 1) * TILE;
+            const int f = syn24_stream(t);
+            int f1 = 0;
+            Look l{0.0, 0.0, {0.0, 0.0}};
+            issue(t, f, l, f1, next_use);
+            const Syn24Part p = syn24_axes<true>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
+            const Mixed mx = mixed_derivs(T, wy, wz, tid, owny, ownz, ih);
+            double off = Gxy * mx.dxy;
+            off = fma(Gxz, mx.dxz, off);
+            off = fma(Gyz, mx.dyz, off);
+            const double lap = fma(2.0, off, p.diag);
+            stg(stash_base(10 + f), s8, lap);
+            emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, lap, halpha, l.unext), l.eo);
+            store_tile<NPLAN, NEXT_USE>(tiles + ((t + 1) & 1) * TILE, fp, pv, tid);
+            __syncthreads();
+        };
+        // pass over a variable without second derivatives (23..10)
+        auto pass_light = [&](int t) {
+            const double* T = tiles + (t & 1) * TILE;
+            const int f = syn24_stream(t);
+            int f1 = 0;
+            Look l{0.0, 0.0, {0.0, 0.0}};
+            issue(t, f, l, f1, UseFace{});
+            const Syn24Part p = syn24_axes<false>(T, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
+            emit<EPI>(a, nb, f, b, o8, p8, syn24_combine(p, f, l.lap, halpha, l.unext), l.eo);
+            if (t + 1 < NSTREAM) {
+                store_tile<NPLAN, PLAN_FACE>(tiles + ((t + 1) & 1) * TILE, fp, pv, tid);
+                __syncthreads();
+            }
+        };
+
+        {   // pass 0: gradient of variable 10 only
+            const int f = syn24_stream(0), f1 = syn24_stream(1);
+            prefetch<NPLAN, PLAN_FACE, ZIN>(pv, fp, var_base(f), tid, virt_base(f));
+            store_tile<NPLAN, PLAN_FACE>(tiles, fp, pv, tid);
+            __syncthreads();
+            prefetch<NPLAN, PLAN_EDGE, ZIN>(pv, fp, var_base(f1), tid, virt_base(f1));
+            nx = d1_at(tiles, c, 1, ih); ny = d1_at(tiles, c, RS, ih); nz = d1_at(tiles, c, PS, ih);
+            store_tile<NPLAN, PLAN_EDGE>(tiles + TILE, fp, pv, tid);
+            __syncthreads();
+        }
+#pragma unroll 1
+        for (int t = 1; t < 10; ++t) pass_d2(t, UseEdge{});
+        pass_d2(10, UseFace{});
+#pragma unroll 1
+        for (int t = 11; t < NSTREAM; ++t) pass_light(t);
     }
 }
 
@@ -284,7 +253,6 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, con
         const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
         from[m] = tidx(kk, jj, ii);                      // where this thread's output elements sit in the tile
     }
-    double cv[CPRE];
     __syncthreads();                                 // the box plan is complete; the plan has left the staging area
 #pragma unroll 1
     for (int v = v0; v < nvar; v += stride) {
@@ -292,7 +260,8 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, con
         double pv[PLAN_FULL];
 #pragma unroll
         for (int m = 0; m < PLAN_FULL; ++m) pv[m] = ldg(base, off[m]);
-        commit<true, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, base, tid);
+        store_tile<PLAN_FULL, PLAN_FULL>(tile, fp, pv, tid);
+        if (bi.cs[0] >= 0) interp_boxes(tile, scratch, bi, base, tid);   // uniform
         __syncthreads();
         double* out = padded + ((int64_t)v * nb + b) * PBLK;
 #pragma unroll
@@ -307,8 +276,6 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, con
 // Level-ordered ghost fill, centred variant: launched once per level, coarsest first; `blocks` lists
 // the blocks of that level.  Copies and injections as in k_unzip; boxes that come from a coarser
 // leaf are interpolated from that leaf's padded block, which an earlier launch has written.
-// SOURCES: only the source leaves are filled, into a compact array indexed by src_slot.
-template <bool SOURCES>
 __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const int32_t* __restrict__ blocks, int nvar,
                                                             const double* __restrict__ zipped, double* padded)
 {
@@ -321,7 +288,6 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const
     const int stride = nvar < NXCD ? nvar : NXCD;
     const int64_t q = blockIdx.x / stride, b = blocks[q], nb = tr.nb;
     const int v0 = (int)(blockIdx.x - q * stride);
-    const int64_t nout = SOURCES ? tr.n_src : nb;
     load_block_info(bi, tr, b, tid);
     __syncthreads();
     if (tid == 0) make_box_plan(bi, true);
@@ -337,8 +303,6 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const
         const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
         from[m] = tidx(kk, jj, ii);
     }
-    double cv[CPRE];
-    const int64_t oslot = SOURCES ? (int64_t)tr.src_slot[b] : b;
     __syncthreads();                                 // the box plan is complete; the plan has left the staging area
 #pragma unroll 1
     for (int v = v0; v < nvar; v += stride) {
@@ -346,11 +310,10 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const
         double pv[PLAN_FULL];
 #pragma unroll
         for (int m = 0; m < PLAN_FULL; ++m) pv[m] = ldg(base, off[m]);
-        commit<false, PLAN_FULL, PLAN_FULL>(tile, scratch, bi, fp, pv, cv, false, base, tid);   // stores only
-        if (SOURCES) interp_boxes_centred<false>(tile, scratch, bi, padded + (int64_t)v * nout * PBLK, tid);
-        else interp_boxes_centred<true>(tile, scratch, bi, padded + (int64_t)v * nout * PBLK, tid);
+        store_tile<PLAN_FULL, PLAN_FULL>(tile, fp, pv, tid);
+        interp_boxes_centred(tile, scratch, bi, padded + (int64_t)v * nb * PBLK, tid);
         __syncthreads();
-        double* out = padded + ((int64_t)v * nout + oslot) * PBLK;
+        double* out = padded + ((int64_t)v * nb + b) * PBLK;
 #pragma unroll
         for (int m = 0; m < PLAN_FULL; ++m) {
             const int p = tid + m * NTHREADS;
@@ -442,6 +405,124 @@ __global__ __launch_bounds__(NTHREADS) void k_virtual(DeviceTree tr, int nvar, c
     }
 }
 
+// Virtual blocks with the centred ghost rule.  The value at a fine position inside a leaf L that is one level coarser
+// is the centred six-point stencil on the coarse lattice around it, nodes c0 - 2 .. c0 + 3 with c0 = f / 2, and nodes
+// outside L are ghost points of L.  A child octant o of L therefore needs, per axis, the nine coarse nodes
+// 4 o - 2 .. 4 o + 6: a 9^3 part of L's padded block, which is gathered here straight from the zipped array and from
+// the virtual blocks of L's own level (a plan of 729 sources, made once per workgroup from L's table row and shared
+// by all variables), so launches go level by level, coarsest first.  Then the same three passes as in k_virtual,
+// with nine nodes per line (81, 72 and 64 lines: a lane takes a second line where there are more than 64).
+constexpr int CN = 9;                                // coarse nodes per axis
+constexpr int CRS = CN, CPS = CN * CN + 7;           // row and plane stride of a wavefront's staging array: 88 = 24 (mod 32)
+constexpr int CSTAGE = CN * CPS;
+
+// the eight fine values of a line with nine nodes v (node n is coarse node 4 o - 2 + n): even f passes node c0 through,
+// odd f takes nodes c0 - 2 .. c0 + 3 with the centred weights, acc = w0 v, then five fma (as centred_line)
+__device__ __forceinline__ void fine_line_centred(const double (&v)[CN], double (&r)[8])
+{
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        r[2 * n] = v[n + 2];
+        double acc = c_lag[12] * v[n];
+#pragma unroll
+        for (int m = 1; m < 6; ++m) acc = fma(c_lag[12 + m], v[n + m], acc);
+        r[2 * n + 1] = acc;
+    }
+}
+
+__global__ __launch_bounds__(NTHREADS) void k_virtual_centred(DeviceTree tr, const int32_t* __restrict__ list, int64_t nlist, int nvar,
+                                                              const double* __restrict__ zipped, double* virt)
+{
+    __shared__ double staging[8][CSTAGE];
+    __shared__ uint32_t plan[CN * CN * CN];          // byte offsets of the 729 sources, bit 0: virtual block
+    __shared__ int32_t gt[27 * 5];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int64_t w = block_of_workgroup(blockIdx.x), nb = tr.nb;
+    if (w >= nlist) return;                          // uniform
+    const int64_t q = list[w];
+    const int64_t leaf = tr.vblk[2 * q];
+    const int oct = tr.vblk[2 * q + 1];
+    if (tid < 27 * 5) gt[tid] = tr.ghost_v[leaf * (27 * 5) + tid];
+    __syncthreads();
+    for (int p = tid; p < CN * CN * CN; p += NTHREADS) {
+        const int nz = p / (CN * CN), r = p - nz * CN * CN, ny = r / CN, nx = r - ny * CN;
+        // position in L's padded block: coarse node 4 o - 2 + n, shifted by the three ghost layers
+        const int ii = 4 * (oct & 1) + 1 + nx, jj = 4 * ((oct >> 1) & 1) + 1 + ny, kk = 4 * (oct >> 2) + 1 + nz;
+        const int rx = ii < PAD ? 0 : (ii < PAD + NPT ? 1 : 2);
+        const int ry = jj < PAD ? 0 : (jj < PAD + NPT ? 1 : 2);
+        const int rz = kk < PAD ? 0 : (kk < PAD + NPT ? 1 : 2);
+        const int lx = ii - PAD + (1 - rx) * NPT, ly = jj - PAD + (1 - ry) * NPT, lz = kk - PAD + (1 - rz) * NPT;
+        plan[p] = ghost_source(&gt[(rz * 9 + ry * 3 + rx) * 5], rx, ry, rz, lx, ly, lz);   // the centre entry is L itself
+    }
+    __syncthreads();
+    double* A = staging[wave];
+    const int hi = lane >> 3, lo = lane & 7;
+    const int64_t in_stride = nb * BLK, out_stride = tr.n_virt * BLK;
+    double* out = virt + q * BLK + lane;
+    // this lane's share of the gather: elements lane, lane + 64, ... of the 729
+    constexpr int NG = (CN * CN * CN + 63) / 64;     // 12
+    uint32_t off[NG];
+    int dst[NG];
+#pragma unroll
+    for (int m = 0; m < NG; ++m) {
+        const int p = min(lane + 64 * m, CN * CN * CN - 1);
+        const int nz = p / (CN * CN), r = p - nz * CN * CN, ny = r / CN;
+        off[m] = plan[p];
+        dst[m] = nz * CPS + ny * CRS + (r - ny * CN);
+    }
+    auto gather = [&](double (&g)[NG], int v) {
+        const double* base = zipped + v * in_stride;
+        const double* vbase = virt + v * out_stride;
+#pragma unroll
+        for (int m = 0; m < NG; ++m) g[m] = ldg((off[m] & 1u) ? vbase : base, off[m] & ~1u);
+    };
+    double nxt[NG];
+    if (wave < nvar) gather(nxt, wave);
+#pragma unroll 1
+    for (int v = wave; v < nvar; v += 8) {
+#pragma unroll
+        for (int m = 0; m < NG; ++m) A[dst[m]] = nxt[m];         // the last element is stored twice by the lanes past 729
+        if (v + 8 < nvar) gather(nxt, v + 8);
+        __builtin_amdgcn_wave_barrier();
+        double c[CN], r[8];
+        // x pass: lines (cz, cy), 81 of them; in place (a lane writes the first eight positions of the row it has read)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int line = lane + 64 * h;
+            if (line < CN * CN) {
+                double* row = A + (line / CN) * CPS + (line % CN) * CRS;
+#pragma unroll
+                for (int m = 0; m < CN; ++m) c[m] = row[m];
+                fine_line_centred(c, r);
+#pragma unroll
+                for (int m = 0; m < 8; ++m) row[m] = r[m];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        // y pass: lines (cz, tx), 72 of them; in place
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int line = lane + 64 * h;
+            if (line < CN * 8) {
+                double* col = A + (line >> 3) * CPS + (line & 7);
+#pragma unroll
+                for (int m = 0; m < CN; ++m) c[m] = col[m * CRS];
+                fine_line_centred(c, r);
+#pragma unroll
+                for (int m = 0; m < 8; ++m) col[m * CRS] = r[m];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        // z pass: lines (ty, tx) = (hi, lo)
+#pragma unroll
+        for (int m = 0; m < CN; ++m) c[m] = A[m * CPS + hi * CRS + lo];
+        fine_line_centred(c, r);
+#pragma unroll
+        for (int m = 0; m < 8; ++m) out[v * out_stride + m * (NPT * NPT)] = r[m];
+        __builtin_amdgcn_wave_barrier();                         // the next variable's gather overwrites the array
+    }
+}
+
 __global__ __launch_bounds__(NTHREADS) void k_zip(int64_t nblocks, const double* __restrict__ padded, double* __restrict__ zipped)
 {
     const int tid = threadIdx.x;
@@ -451,36 +532,25 @@ __global__ __launch_bounds__(NTHREADS) void k_zip(int64_t nblocks, const double*
     zipped[q * BLK + tid] = padded[q * PBLK + ((k + PAD) * NP + (j + PAD)) * NP + (i + PAD)];
 }
 
-template <int KIND, bool ZIN, int EPI, bool CENTRED = false>
+template <int KIND, bool ZIN, int EPI>
 hipError_t launch_one(const DeviceTree& t, const RhsArgs& a, hipStream_t s)
 {
-    if constexpr (KIND == OT_RHS_SYN24 && ZIN && CENTRED) {
-        hipLaunchKernelGGL((k_rhs<KIND, true, EPI, CENTRED, true>), dim3(grid_for_blocks(t.n_sched)), dim3(NTHREADS), 0, s, t, a);
-    } else if constexpr (KIND == OT_RHS_SYN24 && ZIN) {
+    if constexpr (KIND == OT_RHS_SYN24 && ZIN) {
         // sibling pairs in the two-block kernel, the few remaining blocks one per workgroup
         const hipError_t e = launch_rhs_pairs(t, static_cast<Epilogue>(EPI), a, t.pairs, t.n_pairs, s);
         if (e != hipSuccess) return e;
         if (t.n_singles > 0)
-            hipLaunchKernelGGL((k_rhs<KIND, true, EPI, false, true>), dim3(grid_for_blocks(t.n_singles)), dim3(NTHREADS), 0, s, t, a);
-    } else
-        hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, CENTRED, false>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
+            hipLaunchKernelGGL((k_rhs<KIND, true, EPI, true>), dim3(grid_for_blocks(t.n_singles)), dim3(NTHREADS), 0, s, t, a);
+    } else {
+        hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, false>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
+    }
     return hipGetLastError();
 }
 
 template <int KIND>
-hipError_t launch_kind(const DeviceTree& t, bool zin, bool centred, Epilogue ep, const RhsArgs& a, hipStream_t s)
+hipError_t launch_kind(const DeviceTree& t, bool zin, Epilogue ep, const RhsArgs& a, hipStream_t s)
 {
-    if (centred) {
-        if (!zin || !a.pad_src) return hipErrorInvalidValue;
-        switch (ep) {
-        case kOutZipped: return launch_one<KIND, true, kOutZipped, true>(t, a, s);
-        case kRkFirst: return launch_one<KIND, true, kRkFirst, true>(t, a, s);
-        case kRkMiddle: return launch_one<KIND, true, kRkMiddle, true>(t, a, s);
-        case kRkLast: return launch_one<KIND, true, kRkLast, true>(t, a, s);
-        default: return hipErrorInvalidValue;
-        }
-    }
-    if (zin && KIND == OT_RHS_SYN24 && !a.virt && t.n_virt > 0) return hipErrorInvalidValue;
+    if (zin && !a.virt && t.n_virt > 0) return hipErrorInvalidValue;
     if (!zin) {
         switch (ep) {
         case kOutPadded: return launch_one<KIND, false, kOutPadded>(t, a, s);
@@ -509,19 +579,15 @@ hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, dou
     return hipGetLastError();
 }
 
-hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, bool sources_only, int nvar,
-                                const double* zipped, double* padded, hipStream_t s)
+hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, int nvar, const double* zipped, double* padded,
+                                hipStream_t s)
 {
     if (t.nb <= 0 || nvar <= 0) return hipSuccess;
     for (int l = 0; l < 20; ++l) {                   // coarsest level first; the stream orders the launches
         const int64_t n = level_start[l + 1] - level_start[l];
         if (n <= 0) continue;
-        if (sources_only)
-            hipLaunchKernelGGL(k_unzip_centred<true>, dim3((unsigned)(n * (nvar < NXCD ? nvar : NXCD))), dim3(NTHREADS), 0, s, t,
-                               t.src_by_level + level_start[l], nvar, zipped, padded);
-        else
-            hipLaunchKernelGGL(k_unzip_centred<false>, dim3((unsigned)(n * (nvar < NXCD ? nvar : NXCD))), dim3(NTHREADS), 0, s, t,
-                               t.by_level + level_start[l], nvar, zipped, padded);
+        hipLaunchKernelGGL(k_unzip_centred, dim3((unsigned)(n * (nvar < NXCD ? nvar : NXCD))), dim3(NTHREADS), 0, s, t,
+                           t.by_level + level_start[l], nvar, zipped, padded);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -535,6 +601,21 @@ hipError_t launch_virtual(const DeviceTree& t, int nvar, const double* zipped, d
     return hipGetLastError();
 }
 
+hipError_t launch_virtual_centred(const DeviceTree& t, const int64_t* vlevel_start, int nvar, const double* zipped, double* virt,
+                                   hipStream_t s)
+{
+    if (t.n_virt <= 0 || nvar <= 0) return hipSuccess;
+    for (int l = 0; l < 20; ++l) {                   // coarsest level first: a level's virtual blocks read those of the level before
+        const int64_t n = vlevel_start[l + 1] - vlevel_start[l];
+        if (n <= 0) continue;
+        hipLaunchKernelGGL(k_virtual_centred, dim3(grid_for_blocks(n)), dim3(NTHREADS), 0, s, t, t.vlist + vlevel_start[l], n, nvar,
+                           zipped, virt);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, double* zipped, hipStream_t s)
 {
     const int64_t n = t.nb * nvar;
@@ -543,15 +624,14 @@ hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, doubl
     return hipGetLastError();
 }
 
-hipError_t launch_rhs(const DeviceTree& t, ot_rhs_kind kind, bool in_zipped, bool centred, Epilogue ep, const RhsArgs& args,
-                      hipStream_t s)
+hipError_t launch_rhs(const DeviceTree& t, ot_rhs_kind kind, bool in_zipped, Epilogue ep, const RhsArgs& args, hipStream_t s)
 {
     if (t.nb <= 0) return hipSuccess;
     switch (kind) {
-    case OT_RHS_DERIVS: return launch_kind<OT_RHS_DERIVS>(t, in_zipped, centred, ep, args, s);
-    case OT_RHS_WAVE: return launch_kind<OT_RHS_WAVE>(t, in_zipped, centred, ep, args, s);
-    case OT_RHS_BURGERS: return launch_kind<OT_RHS_BURGERS>(t, in_zipped, centred, ep, args, s);
-    case OT_RHS_SYN24: return launch_kind<OT_RHS_SYN24>(t, in_zipped, centred, ep, args, s);
+    case OT_RHS_DERIVS: return launch_kind<OT_RHS_DERIVS>(t, in_zipped, ep, args, s);
+    case OT_RHS_WAVE: return launch_kind<OT_RHS_WAVE>(t, in_zipped, ep, args, s);
+    case OT_RHS_BURGERS: return launch_kind<OT_RHS_BURGERS>(t, in_zipped, ep, args, s);
+    case OT_RHS_SYN24: return launch_kind<OT_RHS_SYN24>(t, in_zipped, ep, args, s);
     default: return hipErrorInvalidValue;
     }
 }

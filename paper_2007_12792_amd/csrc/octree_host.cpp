@@ -250,32 +250,6 @@ void make_level_lists(HostTree& t)
     t.src_by_level.assign(n_src, 0);
     for (size_t b = 0; b < nb; ++b)
         if (t.src_slot[b] >= 0) t.src_by_level[scount[t.leaves[b].level]++] = static_cast<int32_t>(b);
-
-    // launch order of the 24-field kernel: chunks without / with a coarser source, dealt in proportion
-    std::vector<int32_t> part[2];
-    for (size_t b = 0; b < nb; ++b) {
-        const bool has = t.coarse[b * kCoarseRow + 29] > 0;   // a coarser source that covers more than a corner
-        part[has].push_back(static_cast<int32_t>(b) | (has ? kSchedCoarse : 0));
-    }
-    // dealt in units of one chunk per XCD, so that every XCD meets the two kinds in the same order
-    constexpr size_t kUnit = static_cast<size_t>(kSchedChunk) * kSchedXcds;
-    size_t nunit[2], done[2] = {0, 0};
-    for (int p = 0; p < 2; ++p) {
-        while (part[p].size() % kUnit) part[p].push_back(-1);
-        nunit[p] = part[p].size() / kUnit;
-    }
-    t.sched.clear();
-    t.sched.reserve(part[0].size() + part[1].size());
-    while (done[0] < nunit[0] || done[1] < nunit[1]) {
-        // take from the part that is further behind its share (done / nunit smaller); measured on the
-        // 102,075-block tree against all chunks of one part first: 75.0 ms per step against 78.4 and 79.2
-        int p = 0;
-        if (done[0] >= nunit[0]) p = 1;
-        else if (done[1] < nunit[1] && done[1] * nunit[0] < done[0] * nunit[1]) p = 1;
-        const int32_t* src = part[p].data() + done[p] * kUnit;
-        t.sched.insert(t.sched.end(), src, src + kUnit);
-        ++done[p];
-    }
 }
 
 // needs src_slot (make_level_lists)
@@ -313,6 +287,13 @@ void make_virtual_blocks(HostTree& t)
                 t.vblk.push_back(t.vsrc[s * kVsrcRow]);
                 t.vblk.push_back(c);
             }
+    // by level
+    int64_t count[21] = {};
+    for (int32_t q = 0; q < n; ++q) ++count[t.leaves[t.vblk[2 * q]].level + 2];      // its own level + 1
+    for (int l = 1; l <= 20; ++l) count[l] += count[l - 1];
+    for (int l = 0; l <= 20; ++l) t.vlevel_start[l] = count[l];
+    t.vlist.assign(n, 0);
+    for (int32_t q = 0; q < n; ++q) t.vlist[count[t.leaves[t.vblk[2 * q]].level + 1]++] = q;
     t.ghost_v = t.ghost;
     for (size_t b = 0; b < nb; ++b)
         for (int dir = 0; dir < kDirs; ++dir) {

@@ -26,6 +26,7 @@ struct HostTree {
     //   [16]     number of face neighbours that are coarser, then [17..28] that many {face, leaf id}
     //            pairs, face = 2*axis + (0 low side, 1 high side);
     //   [29]     number of sources in front of the corner-only ones.
+    // Read by the kernels that write padded blocks (unzip, unzip_centred).
     std::vector<int32_t> coarse;
     // Block ids sorted by level (ascending, Morton order within a level): blocks of level l are
     // by_level[level_start[l] .. level_start[l+1]).  Used by the level-ordered ghost fill.
@@ -36,14 +37,6 @@ struct HostTree {
     // src_by_level / src_level_start list them by level like by_level / level_start.
     std::vector<int32_t> src_slot, src_by_level;
     int64_t src_level_start[21] = {};
-    // Launch order of the 24-field kernel.  The blocks are split by whether they take ghost values from a
-    // coarser leaf other than into a corner of the padded block, which that kernel does not read (those that
-    // do not run a path compiled without the interpolation).  Each part, in Morton order, is cut into chunks of
-    // kSchedChunk entries and these into units of kSchedXcds chunks (the last unit padded with -1); the units of
-    // the two parts are dealt into one sequence in proportion, so that both kinds of work are on the device
-    // together from the first to the last workgroup and every XCD (which receives every kSchedXcds-th chunk)
-    // meets them in the same order.  Entry = block id, | kSchedCoarse for the second part.
-    std::vector<int32_t> sched;
     // "Virtual blocks".  Where the same-level neighbour octant of a block does not exist because its parent L is
     // a leaf, the ghost values in that direction are interpolated inside L, and what they are depends only on L's
     // data and on the fine position inside L, not on which block asks.  Such an octant can therefore be filled
@@ -55,8 +48,12 @@ struct HostTree {
     //   vblk    [n_virt][2]        per virtual block {source leaf id, child octant}
     //   ghost_v [nb][27][5]        the ghost table with every coarser entry replaced by {kVirtual, virtual block}
     //   n_virt                     number of virtual blocks
-    std::vector<int32_t> vsrc, vblk, ghost_v;
+    //   vlist   [n_virt]           virtual blocks sorted by level (the level of a virtual block is its source leaf's
+    //                              plus one): level l occupies vlist[vlevel_start[l] .. vlevel_start[l+1]).  With the
+    //                              centred ghost rule a level's virtual blocks read those of the level before.
+    std::vector<int32_t> vsrc, vblk, ghost_v, vlist;
     int64_t n_virt = 0;
+    int64_t vlevel_start[21] = {};
     // Sibling pairs for the two-block kernel of the 24-field system: `pairs` lists the first block of every two
     // leaves that are the lower and upper x child of one parent (they follow each other in Morton order), `singles`
     // every other block (a leaf whose x sibling is subdivided).  Both in Morton order; together they cover every

@@ -17,18 +17,15 @@ constexpr int K_COARSER = 2, K_SAME = 0, K_VIRT = 3;
 // (i, k): the eight x-contiguous values of four consecutive k planes then fall into 32 different
 // 8-byte banks, and shifting the access by any stencil offset keeps that property.
 // wavefronts per SIMD the right-hand-side kernels are compiled for: the 24-field kernel 4 (128 VGPRs per lane, two
-// workgroups share a compute unit, which is also what its LDS allows); the other kinds 8 (64 VGPRs, four workgroups),
-// except with the centred ghost rule, whose interpolation does not fit 64 registers without spilling (6: 80 VGPRs,
-// three workgroups; a kernel of this size that spills is slower than one with fewer workgroups)
-constexpr int waves_per_simd(int kind, bool centred) { return kind == OT_RHS_SYN24 ? 4 : (centred ? 6 : 8); }
+// workgroups share a compute unit, which is also what its LDS allows); the other kinds 8 (64 VGPRs, four workgroups)
+constexpr int waves_per_simd(int kind) { return kind == OT_RHS_SYN24 ? 4 : 8; }
 constexpr int RS = NP;                   // 14
 constexpr int PS = NP * RS + 4;          // 200
 constexpr int TILE = NP * PS;            // 14 planes
 constexpr int WZ = NPT * PS;             // D1_z u on [8 k][14 jj][14 ii]
 constexpr int YPS = NPT * RS + 8;        // plane stride of the D1_y array, 120 = 24 (mod 32)
 constexpr int WY = NPT * YPS;            // D1_y u on [8 k][8 j][14 ii]
-// wy and wz together need 2,560 doubles; the ghost interpolation stages several coarser leaves at
-// once in the same area and profits from the 448 more that still let two workgroups share a CU
+// staging area of the box interpolation in k_unzip: several coarser leaves at once
 constexpr int SCRATCH = WZ + WY + 448;
 
 constexpr int ROUND_SRC = 4;                 // source leaves per round (one register each while in flight)
@@ -47,7 +44,6 @@ struct BlockInfo {       // per-workgroup copy of the block's table rows
     int32_t cs[32];      // [0..15] coarse sources: {leaf id, packed region range} x 8, id < 0 ends the
                          // list, corner-only sources last; [16] number of coarser faces, [17..28] {face, leaf id}
                          // pairs; [29] number of sources in front of the corner-only ones
-    int32_t slot[8];     // centred ghost rule: where the padded block of coarse source s sits (src_slot of its id)
     uint32_t level, ax, ay, az;
     double lag[36];
     BoxPlan box;         // filled by make_box_plan()
@@ -105,10 +101,6 @@ __device__ __forceinline__ void load_block_info(BlockInfo& bi, const DeviceTree&
     if (tid < 27 * 5) bi.gt[tid] = (VIRT ? tr.ghost_v : tr.ghost)[b * (27 * 5) + tid];
     if (tid >= 192 && tid < 192 + 36) bi.lag[tid - 192] = c_lag[tid - 192];
     if (tid >= 256 && tid < 256 + 32) bi.cs[tid - 256] = tr.coarse[b * 32 + (tid - 256)];
-    if (tid >= 384 && tid < 384 + 8) {
-        const int32_t id = tr.coarse[b * 32 + 2 * (tid - 384)];
-        bi.slot[tid - 384] = id >= 0 ? tr.src_slot[id] : -1;
-    }
     if (tid == 320) {
         const ot_leaf lf = tr.leaves[b];
         bi.level = lf.level; bi.ax = lf.ix; bi.ay = lf.iy; bi.az = lf.iz;
@@ -178,7 +170,6 @@ struct FillPlan {
     __device__ __forceinline__ void set_dst(int m, int v) { dstp[m >> 1] = (m & 1) ? (dstp[m >> 1] | ((uint32_t)v << 16)) : (uint32_t)v; }
 };
 static_assert(TILE < 65536, "tile indices are packed in pairs");
-static_assert(SCRATCH >= 1024 + 2 * 512, "face interpolation staging: 8 x 128 per-wavefront + 2 x 512 shared");
 
 // Where the point (lx, ly, lz) of the same-level octant in direction (rx, ry, rz) - 1 comes from, given that
 // direction's table entry e (not a coarser one): byte offset into one variable's zipped array (same level: copy;

@@ -1,0 +1,133 @@
+// Host-only check of the derived tables of the library's tree (no GPU, no HIP call): the per-block list of
+// coarser sources (corner-only sources last, their count recorded), the virtual blocks with the ghost table that
+// names them, and the sibling pairs.  Built with g++ together with csrc/octree_host.cpp by tests/test_library_host.py.
+#include <cmath>
+#include <cstdio>
+#include <vector>
+
+#include "kernels.hpp"
+#include "octree_host.hpp"
+
+using namespace octfd;
+
+static int fail(const char* what, long b) { std::printf("FAILED: %s (block %ld)\n", what, b); return 1; }
+
+static int check(const HostTree& t)
+{
+    const long nb = static_cast<long>(t.leaves.size());
+    long n_coarse_kind = 0;
+    for (long b = 0; b < nb; ++b) {
+        const int32_t* row = &t.coarse[b * kCoarseRow];
+        // sources named by the ghost table, each exactly once
+        int n = 0;
+        while (n < 8 && row[2 * n] >= 0) ++n;
+        int seen_in_table = 0;
+        for (int dir = 0; dir < kDirs; ++dir) {
+            const int32_t* e = &t.ghost[(b * kDirs + dir) * kEntry];
+            if (e[0] != kCoarser) continue;
+            int hit = 0;
+            for (int s = 0; s < n; ++s) hit += row[2 * s] == e[1];
+            if (hit != 1) return fail("a coarser source of the ghost table is not listed exactly once", b);
+            ++seen_in_table;
+        }
+        if ((n > 0) != (seen_in_table > 0)) return fail("source list and ghost table disagree", b);
+        // corner-only sources (ghost part on every axis) come last, and [29] counts the others
+        int first_corner = n;
+        for (int s = 0; s < n; ++s) {
+            const int pk = row[2 * s + 1];
+            bool corner = true;
+            for (int ax = 0; ax < 3; ++ax) {
+                const int lo = (pk >> (4 * ax)) & 3, hi = (pk >> (4 * ax + 2)) & 3;
+                if (lo > hi) return fail("empty range", b);
+                corner = corner && lo == hi && lo != 1;
+            }
+            if (corner && first_corner == n) first_corner = s;
+            if (!corner && first_corner != n) return fail("a corner-only source precedes another source", b);
+        }
+        if (row[29] != first_corner) return fail("count of the sources that are not corner-only", b);
+        n_coarse_kind += row[29] > 0;
+    }
+    // virtual blocks: every coarser entry of the ghost table has become a virtual block that is the right child
+    // octant of the right source leaf; every virtual block is used, listed once per level, one level below its source
+    const long nv = static_cast<long>(t.n_virt);
+    if (static_cast<long>(t.vblk.size()) != 2 * nv || static_cast<long>(t.vlist.size()) != nv || t.ghost_v.size() != t.ghost.size())
+        return fail("sizes of the virtual-block tables", -1);
+    std::vector<int> used(nv, 0);
+    for (long b = 0; b < nb; ++b)
+        for (int dir = 0; dir < kDirs; ++dir) {
+            const int32_t* e = &t.ghost[(b * kDirs + dir) * kEntry];
+            const int32_t* v = &t.ghost_v[(b * kDirs + dir) * kEntry];
+            if (e[0] != kCoarser) {
+                for (int m = 0; m < kEntry; ++m)
+                    if (e[m] != v[m]) return fail("an entry that is not coarser was changed", b);
+                continue;
+            }
+            if (v[0] != kVirtual || v[1] < 0 || v[1] >= nv) return fail("a coarser entry is not a virtual block", b);
+            const ot_leaf& o = t.leaves[b];
+            const uint32_t mask = (1u << o.level) - 1;
+            const uint32_t x = (o.ix + (dir % 3 - 1)) & mask, y = (o.iy + ((dir / 3) % 3 - 1)) & mask, z = (o.iz + (dir / 9 - 1)) & mask;
+            const ot_leaf& src = t.leaves[t.vblk[2 * v[1]]];
+            if (t.vblk[2 * v[1]] != e[1]) return fail("source leaf of a virtual block", b);
+            if (src.level + 1 != o.level || src.ix != x >> 1 || src.iy != y >> 1 || src.iz != z >> 1) return fail("a virtual block is not inside its source leaf", b);
+            if (t.vblk[2 * v[1] + 1] != static_cast<int32_t>((x & 1) | ((y & 1) << 1) | ((z & 1) << 2))) return fail("child octant of a virtual block", b);
+            ++used[v[1]];
+        }
+    std::vector<int> listed(nv, 0);
+    for (int l = 0; l < 20; ++l) {
+        if (t.vlevel_start[l] > t.vlevel_start[l + 1]) return fail("level ranges of the virtual blocks", l);
+        for (int64_t q = t.vlevel_start[l]; q < t.vlevel_start[l + 1]; ++q) {
+            const int32_t v = t.vlist[q];
+            if (v < 0 || v >= nv || static_cast<int>(t.leaves[t.vblk[2 * v]].level) + 1 != l) return fail("level of a listed virtual block", v);
+            ++listed[v];
+        }
+    }
+    if (t.vlevel_start[0] != 0 || t.vlevel_start[20] != nv) return fail("level ranges do not cover the virtual blocks", -1);
+    for (long v = 0; v < nv; ++v) {
+        if (!used[v]) return fail("a virtual block that nobody reads", v);
+        if (listed[v] != 1) return fail("a virtual block is not listed exactly once", v);
+        if (v > 0 && (t.vblk[2 * v] < t.vblk[2 * v - 2] || (t.vblk[2 * v] == t.vblk[2 * v - 2] && t.vblk[2 * v + 1] <= t.vblk[2 * v - 1])))
+            return fail("order of the virtual blocks", v);
+    }
+    // sibling pairs and single blocks: every block exactly once; a pair is the lower and upper x child of one parent
+    std::vector<int> times(nb, 0);
+    for (int32_t b : t.pairs) {
+        if (b < 0 || b + 1 >= nb) return fail("pair id", b);
+        const ot_leaf &lo = t.leaves[b], &hi = t.leaves[b + 1];
+        if ((lo.ix & 1) || hi.level != lo.level || hi.ix != lo.ix + 1 || hi.iy != lo.iy || hi.iz != lo.iz) return fail("not an x-sibling pair", b);
+        ++times[b];
+        ++times[b + 1];
+    }
+    for (int32_t b : t.singles) {
+        if (b < 0 || b >= nb) return fail("single id", b);
+        ++times[b];
+        // its x sibling must be subdivided: neither neighbour in storage order completes a pair with it
+        const ot_leaf& o = t.leaves[b];
+        const long sib = (o.ix & 1) ? b - 1 : b + 1;
+        if (sib >= 0 && sib < nb) {
+            const ot_leaf& n = t.leaves[sib];
+            if (n.level == o.level && (n.ix ^ 1) == o.ix && n.iy == o.iy && n.iz == o.iz) return fail("a single block has a leaf as x sibling", b);
+        }
+    }
+    for (long b = 0; b < nb; ++b)
+        if (times[b] != 1) return fail("a block is not covered exactly once by pairs and singles", b);
+    std::printf("blocks %ld, with a coarser source beyond a corner %ld, virtual blocks %ld, pairs %zu, singles %zu\n", nb, n_coarse_kind, nv,
+                t.pairs.size(), t.singles.size());
+    return 0;
+}
+
+int main()
+{
+    // an adaptive tree with two centres (levels 3..6), a uniform one, and one centre near the periodic corner
+    const uint32_t pts[6] = {416961, 715879, 415070, 444683, 374201, 590464};
+    const uint32_t rad[3] = {125829, 125829, 125829};
+    HostTree a, u, c;
+    ot_build_params p{3, 6, 2, pts, rad, 8, 3, 1};
+    if (build_tree(p, a) != OT_OK || check(a)) return 1;
+    ot_build_params q{4, 4, 0, nullptr, nullptr, 8, 3, 1};
+    if (build_tree(q, u) != OT_OK || check(u)) return 1;
+    const uint32_t corner[3] = {1000, 2000, 1040000};
+    const uint32_t rad2[2] = {50000, 60000};
+    ot_build_params r{3, 5, 1, corner, rad2, 8, 3, 1};
+    if (build_tree(r, c) != OT_OK || check(c)) return 1;
+    return 0;
+}

@@ -17,12 +17,15 @@
  *     device.  The caller owns every data array and the workspace.  The library owns only ot_tree
  *     and the device copies of its index tables (released by octree_free).
  *   - device entry points only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
- *     default stream).  They do not synchronise and do not allocate, with one exception: the device
- *     copies of a tree's index tables are a cache inside the opaque handle, which the first device
- *     call on the tree fills (one hipMalloc and synchronous copies; this fails inside a stream
- *     capture).  Call octree_upload beforehand where that matters: after it no device call on the
- *     tree allocates or synchronises.  The device that was current then must be the current one in
- *     every later call on the tree (else OT_E_UNSUPPORTED).
+ *     default stream).  They do not synchronise and do not allocate, with two exceptions.  (1) The
+ *     device copies of a tree's index tables are a cache inside the opaque handle, which the first
+ *     device call on the tree fills (one hipMalloc and synchronous copies; this fails inside a
+ *     stream capture).  Call octree_upload beforehand where that matters.  The device that was
+ *     current then must be the current one in every later call on the tree (else
+ *     OT_E_UNSUPPORTED).  (2) rhs_eval_zipped, which has no workspace argument, keeps the virtual
+ *     blocks of its input (see there) in an array that belongs to the tree; its first call on a
+ *     tree with level jumps allocates that array (a later call with more variables enlarges it).
+ *     rk_step, rk_step_centred and rk_step_static never allocate once the tables are uploaded.
  *   - data arrays hold doubles and must be 8-byte aligned, workspaces 256-byte aligned
  *     (OT_E_BADARG otherwise).
  *   - calls that use the same tree, plan or workspace must not overlap in time.
@@ -147,7 +150,13 @@ int zip(const ot_tree *tree, int nvar, const double *padded_dev, double *zipped_
 /* The three calls above fused: zipped in, zipped right-hand side out, no padded array in memory.
  * Bit-identical to zip(rhs_eval(unzip(.))).  For SYN24 both rhs_eval and rhs_eval_zipped use
  * variables 10..19 of the output array as scratch while they run (each is overwritten with its
- * final value before the call's work completes). */
+ * final value before the call's work completes).
+ * How level jumps are handled: where the same-level neighbour octant of a block does not exist
+ * because its parent L is a leaf, unzip's rule makes the ghost values there a function of L's data
+ * and of the fine position inside L alone.  Such an octant ("virtual block") is therefore filled
+ * once per call, all 8^3 points, x then y then z exactly as unzip interpolates a ghost point, and
+ * the blocks around it copy from it as from a neighbour of their own level.  The virtual blocks of
+ * the input take nvar * (number of virtual blocks) * 4 KB in an array owned by the tree. */
 int rhs_eval_zipped(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
                     const double *zipped_dev, double *rhs_zipped_dev, void *hip_stream);
 
@@ -155,8 +164,8 @@ int rhs_eval_zipped(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *
  *   k1 = F(u), k2 = F(u + dt/2 k1), k3 = F(u + dt/2 k2), k4 = F(u + dt k3),
  *   u <- u + dt/6 (((k1 + 2 k2) + 2 k3) + k4),  every a*k + u evaluated as one fma.
  * u_zipped_dev [nvar][nb][8^3] is updated in place.  workspace_dev must hold at least
- * rk_workspace_bytes() bytes (three zipped state vectors), be 256-byte aligned and not overlap u
- * (OT_E_BADARG otherwise).
+ * rk_workspace_bytes() bytes (three zipped state vectors and the virtual blocks of one, see
+ * rhs_eval_zipped), be 256-byte aligned and not overlap u (OT_E_BADARG otherwise).
  * Ghost values at level jumps follow unzip's rule, whose outermost row extrapolates by half a
  * coarse cell.  That row makes level jumps unstable for wave propagation over many steps (the wave
  * system on a three-level tree, sigma = 0.4: max |u| grows past 1e9 by t = 1); for evolutions
@@ -171,7 +180,8 @@ int rk_step(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, 
  * until the process ends.  Same arithmetic and results as rk_step.  The call allocates nothing and
  * does not synchronise; octree_upload(tree) must have been called on the current device before
  * (OT_E_UNSUPPORTED otherwise), and rk_workspace_bytes(tree, kind) must not exceed
- * OT_STATIC_WORKSPACE_BYTES (OT_E_WORKSPACE otherwise; e.g. the wave system on up to 3,400 blocks).
+ * OT_STATIC_WORKSPACE_BYTES (OT_E_WORKSPACE otherwise; the wave system on a three-level tree of 800
+ * blocks needs 25 MB, the 24-field system on the uniform 512-block tree 151 MB).
  * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU race, even
  * on different trees or streams.  Nothing in the array needs clearing between calls (every word
  * a step reads it has written before). */
@@ -190,10 +200,11 @@ int rk_step_static(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *p
  * jumps stay stable for wave propagation over long times.
  *
  * rk_step_centred is rk_step with F = zip(rhs_eval(unzip_centred(.))), bit-identical to that
- * composition, but only the padded blocks of the leaves that serve as coarser sources are ever
- * written to memory (level by level, before each stage); everything else is fused as in rk_step.
- * Its workspace holds three zipped state vectors followed by those padded blocks
- * (rk_centred_workspace_bytes), 256-byte aligned. */
+ * composition.  It differs from rk_step only in how the virtual blocks (see rhs_eval_zipped) are
+ * filled before each stage: with the centred stencils, level by level, each from the part of its
+ * source leaf's padded block that it needs (gathered from the zipped vector and from the virtual
+ * blocks of the level before).  Same stage kernels, same workspace (rk_centred_workspace_bytes
+ * equals rk_workspace_bytes), and within a few per cent of rk_step's time. */
 int unzip_centred(const ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev, void *hip_stream);
 int rk_centred_workspace_bytes(const ot_tree *tree, ot_rhs_kind kind, size_t *bytes);
 int rk_step_centred(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params, double dt,

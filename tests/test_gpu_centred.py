@@ -75,9 +75,11 @@ def test_rk_step_centred(orc, dev, name):
 
 def test_two_ghost_rules_on_a_plane_wave_over_many_steps(dev):
     """u = sin(2 pi (x + 2y) - omega t) solves the wave system exactly.  On an adaptive tree the
-    centred rule keeps the error small and bounded over a thousand steps; the clamped rule (half-cell
-    extrapolation at level jumps) starts 25 times worse.  Per-step parity with the oracle is
-    established by the tests above; this one measures the two rules against the exact solution."""
+    centred rule keeps the error small and bounded over a thousand steps (t = 1); the clamped rule (half-cell
+    extrapolation at level jumps, a stencil row with sum |w| = 18) starts 25 times worse and is unstable: its
+    error grows by orders of magnitude over the same time.  Per-step parity with the oracle is established by
+    the tests above; this one measures the two rules against the exact solution and pins the known growth of
+    the clamped rule, so that a change in either rule shows."""
     t = octfd.Tree.build(**sd.tree_params("T3", 1))
     x, y, _ = sd.node_coords(t.leaves, dev)
     tp = 2 * np.pi
@@ -88,19 +90,27 @@ def test_two_ghost_rules_on_a_plane_wave_over_many_steps(dev):
         return torch.stack([torch.sin(ph), -om * torch.cos(ph)])
 
     dt = sd.time_step(5)
-    err = {}
-    for rule, nsteps in (("clamped", 64), ("centred", 1024)):
+    err, peak = {}, {}
+    for rule in ("clamped", "centred"):
         u = exact(0.0).contiguous()
-        nbytes = t.rk_centred_workspace_bytes(1) if rule == "centred" else t.rk_workspace_bytes(1)
-        ws = torch.empty(nbytes // 8, dtype=torch.float64, device=dev)
-        for s in range(1, nsteps + 1):
+        ws = torch.empty(t.rk_workspace_bytes(1) // 8, dtype=torch.float64, device=dev)
+        for s in range(1, 1025):
             (t.rk_step_centred if rule == "centred" else t.rk_step)(1, u, dt, ws, sigma=sd.KO_SIGMA)
-            if s in (64, 1024):
+            if s in (64, 256, 512, 1024):
                 err[rule, s] = (u[0] - exact(s * dt)[0]).abs().max().item()
-    print("max error of u after 64 steps: clamped %.3e, centred %.3e; centred after 1024 steps: %.3e"
-          % (err["clamped", 64], err["centred", 64], err["centred", 1024]), flush=True)
+                peak[rule, s] = u[0].abs().max().item()
+    for rule in ("clamped", "centred"):
+        print("%s rule: max error of u after 64 / 256 / 512 / 1024 steps: %s; max |u|: %s"
+              % (rule, "  ".join("%.3e" % err[rule, s] for s in (64, 256, 512, 1024)),
+                 "  ".join("%.3e" % peak[rule, s] for s in (64, 256, 512, 1024))), flush=True)
     assert err["centred", 64] < err["clamped", 64] / 10.0
-    assert err["centred", 1024] < 1e-4
+    assert err["centred", 1024] < 1e-4 and peak["centred", 1024] < 1.001
+    # the clamped rule: accurate to 1e-4 over the first 64 steps; measured 7e-5, 2e-4, 4.5 and 3e9 after 64, 256, 512
+    # and 1024 steps
+    assert err["clamped", 64] < 2e-4
+    assert err["clamped", 256] > 2 * err["clamped", 64]
+    assert err["clamped", 512] > 1.0
+    assert not (peak["clamped", 1024] < 1e3)          # grown beyond any solution of the wave equation, or overflowed
 
 
 def test_centred_step_on_a_uniform_tree_equals_the_clamped_step(dev):

@@ -88,12 +88,11 @@ int ensure_device(const ot_tree* t)
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e);
     // one allocation for all tables, each part 256-byte aligned
     const HostTree& h = t->host;
-    constexpr int kParts = 9;
+    constexpr int kParts = 6;
     auto ibytes = [](const std::vector<int32_t>& v) { return v.size() * sizeof(int32_t); };
-    const void* part[kParts] = {h.leaves.data(), h.ghost.data(), h.coarse.data(), h.by_level.data(), h.ghost_v.data(),
-                                h.vblk.data(), h.vlist.data(), h.pairs.data(), h.singles.data()};
-    const size_t bytes[kParts] = {h.leaves.size() * sizeof(ot_leaf), ibytes(h.ghost), ibytes(h.coarse), ibytes(h.by_level),
-                                  ibytes(h.ghost_v), ibytes(h.vblk), ibytes(h.vlist), ibytes(h.pairs), ibytes(h.singles)};
+    const void* part[kParts] = {h.leaves.data(), h.ghost_v.data(), h.vblk.data(), h.vlist.data(), h.pairs.data(), h.singles.data()};
+    const size_t bytes[kParts] = {h.leaves.size() * sizeof(ot_leaf), ibytes(h.ghost_v), ibytes(h.vblk), ibytes(h.vlist), ibytes(h.pairs),
+                                  ibytes(h.singles)};
     size_t off[kParts + 1] = {0};
     for (int i = 0; i < kParts; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
     char* base = nullptr;
@@ -106,9 +105,9 @@ int ensure_device(const ot_tree* t)
     }
     auto ints = [&](int i) { return reinterpret_cast<const int32_t*>(base + off[i]); };
     t->d_base = base;
-    t->dev = DeviceTree{reinterpret_cast<const ot_leaf*>(base + off[0]), ints(1), ints(2), ints(3), static_cast<int64_t>(h.leaves.size()),
-                        ints(4), ints(5), ints(6), h.n_virt,
-                        ints(7), static_cast<int64_t>(h.pairs.size()), ints(8), static_cast<int64_t>(h.singles.size())};
+    t->dev = DeviceTree{reinterpret_cast<const ot_leaf*>(base + off[0]), static_cast<int64_t>(h.leaves.size()),
+                        ints(1), ints(2), ints(3), h.n_virt,
+                        ints(4), static_cast<int64_t>(h.pairs.size()), ints(5), static_cast<int64_t>(h.singles.size())};
     t->device = dev;
     return resolve_static_workspace(dev);
 }
@@ -148,6 +147,20 @@ int ensure_device(ot_transfer* p)
 DeviceTree dev_view(const ot_tree* t) { return t->dev; }
 
 bool kind_ok(int k) { return k >= OT_RHS_DERIVS && k <= OT_RHS_SYN24; }
+
+// the tree's own array of virtual blocks, for the calls that have no workspace argument: at least `bytes` large
+int ensure_virtual_scratch(const ot_tree* tree, size_t bytes)
+{
+    if (bytes <= tree->virt_bytes) return OT_OK;
+    hipError_t e = hipSuccess;
+    if (tree->d_virt) e = hipFree(tree->d_virt);   // synchronises with earlier work on the old array
+    tree->d_virt = nullptr;
+    tree->virt_bytes = 0;
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&tree->d_virt), bytes);
+    if (e != hipSuccess) return hip_fail(e);
+    tree->virt_bytes = bytes;
+    return OT_OK;
+}
 
 // bytes of the virtual blocks of one input vector of a kind
 size_t virtual_bytes(const ot_tree* t, int kind)
@@ -251,21 +264,29 @@ int ot_rhs_nvar_out(ot_rhs_kind kind)
     }
 }
 
-int unzip(const ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
+// both ghost rules: fill the virtual blocks of the input (that is where the rules differ), then gather
+static int unzip_any(const ot_tree* tree, bool centred, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
 {
     if (!tree || nvar <= 0 || !zipped_dev || !padded_dev || !aligned8(zipped_dev) || !aligned8(padded_dev)) return OT_E_BADARG;
     if (int rc = ensure_device(tree)) return rc;   // < 2^20 blocks, and the grid is at most 8 workgroups per block
-    hipError_t e = launch_unzip(dev_view(tree), nvar, zipped_dev, padded_dev, static_cast<hipStream_t>(hip_stream));
+    const size_t vbytes = static_cast<size_t>(nvar) * static_cast<size_t>(tree->host.n_virt) * 512 * sizeof(double);
+    if (int rc = ensure_virtual_scratch(tree, vbytes)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const DeviceTree dv = dev_view(tree);
+    hipError_t e = centred ? launch_virtual_centred(dv, tree->host.vlevel_start, nvar, zipped_dev, tree->d_virt, s)
+                           : launch_virtual(dv, nvar, zipped_dev, tree->d_virt, s);
+    if (e == hipSuccess) e = launch_unzip(dv, nvar, zipped_dev, tree->d_virt, padded_dev, s);
     return e == hipSuccess ? OT_OK : hip_fail(e);
+}
+
+int unzip(const ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
+{
+    return unzip_any(tree, false, nvar, zipped_dev, padded_dev, hip_stream);
 }
 
 int unzip_centred(const ot_tree* tree, int nvar, const double* zipped_dev, double* padded_dev, void* hip_stream)
 {
-    if (!tree || nvar <= 0 || !zipped_dev || !padded_dev || !aligned8(zipped_dev) || !aligned8(padded_dev)) return OT_E_BADARG;
-    if (int rc = ensure_device(tree)) return rc;
-    hipError_t e = launch_unzip_centred(dev_view(tree), tree->host.level_start, nvar, zipped_dev, padded_dev,
-                                        static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? OT_OK : hip_fail(e);
+    return unzip_any(tree, true, nvar, zipped_dev, padded_dev, hip_stream);
 }
 
 int zip(const ot_tree* tree, int nvar, const double* padded_dev, double* zipped_dev, void* hip_stream)
@@ -297,15 +318,7 @@ int rhs_eval_zipped(const ot_tree* tree, ot_rhs_kind kind, const ot_rhs_params* 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const DeviceTree dv = dev_view(tree);
     const size_t vbytes = virtual_bytes(tree, kind);
-    if (vbytes > tree->virt_bytes) {      // first call that needs the virtual blocks (or more of them than before)
-        hipError_t e = hipSuccess;
-        if (tree->d_virt) e = hipFree(tree->d_virt);   // synchronises with earlier work on the old array
-        tree->d_virt = nullptr;
-        tree->virt_bytes = 0;
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&tree->d_virt), vbytes);
-        if (e != hipSuccess) return hip_fail(e);
-        tree->virt_bytes = vbytes;
-    }
+    if (int rc = ensure_virtual_scratch(tree, vbytes)) return rc;
     if (vbytes) {
         hipError_t e = launch_virtual(dv, ot_rhs_nvar_in(kind), zipped_dev, tree->d_virt, s);
         if (e != hipSuccess) return hip_fail(e);

@@ -14,7 +14,7 @@
 //
 // Arithmetic follows one fixed IEEE sequence per formula (see octfd.h); the file is compiled with
 // -ffp-contract=off, so a fused multiply-add happens exactly where fma() is written.
-#include "ghost_interp.hpp"
+#include "fill.hpp"
 #include "stencils.hpp"
 #include "syn24.hpp"
 #include "tile.hpp"
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
 
     const int tid = threadIdx.x;
     const int64_t nb = tr.nb;
-    load_block_info<ZIN>(bi, tr, b, tid);
+    load_block_info(bi, tr, b, tid);
     __syncthreads();
 
     int i, j, k;
@@ -223,103 +223,49 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
 
 // ---------------------------------------------------------------- unzip / zip kernels
 
-__global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, const double* __restrict__ zipped, double* __restrict__ padded)
+// unzip as a gather.  With the virtual blocks of the input filled (by k_virtual for the clamped ghost rule, by
+// k_virtual_centred for the centred one), every one of the 2,744 points of a padded block is a copy: of the block's
+// own data, of a same-level or virtual neighbour, or of the coinciding node of a finer neighbour.  A thread owns up to
+// six consecutive-by-512 output positions of the padded block and keeps their sources in registers for all
+// variables; no LDS, no barrier, loads and stores of different variables overlap freely.
+// Workgroup r + G b takes variables r, r + G, r + 2G, ... of block b, G = min(8, nvar): with the workgroups dealt to
+// the eight XCDs in turn, an XCD sees a fixed subset of the variables for consecutive blocks one after the other, so a
+// ghost row it fetches was, or soon will be, an interior row of a block it handles for the same variable and is
+// served by its L2.
+__global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, const double* __restrict__ zipped, const double* __restrict__ virt,
+                                                    double* __restrict__ padded)
 {
-    __shared__ double tile[TILE];
-    __shared__ double scratch[SCRATCH];
-    __shared__ BlockInfo bi;
+    __shared__ int32_t gt[27 * 5];
     const int tid = threadIdx.x;
-    // Workgroup r + G b fills the padded blocks of variables r, r + G, r + 2G, ... of block b, G =
-    // min(8, nvar).  With the workgroups dealt to the eight XCDs in turn, an XCD sees a fixed subset of
-    // the variables for consecutive blocks one after the other, so a ghost row it fetches was, or soon
-    // will be, an interior row of a block it handles for the same variable and is served by its L2
-    // (102,075-block tree, 24 variables: 22 GB fetched per call against 77 GB with the blocks of one
-    // variable launched together).  The fill plan is built once per workgroup and kept in registers.
     const int stride = nvar < NXCD ? nvar : NXCD;
     const int64_t b = blockIdx.x / stride, nb = tr.nb;
     const int v0 = (int)(blockIdx.x - b * stride);
-    load_block_info(bi, tr, b, tid);
+    if (tid < 27 * 5) gt[tid] = tr.ghost_v[b * (27 * 5) + tid];
     __syncthreads();
-    if (tid == 0) make_box_plan(bi, true);
-    FillPlan<PLAN_FULL> fp;
-    fp.src = reinterpret_cast<uint32_t*>(scratch);   // the staging area is free until the first interpolation
-    make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);
     uint32_t off[PLAN_FULL];
-    int from[PLAN_FULL];
 #pragma unroll
     for (int m = 0; m < PLAN_FULL; ++m) {
-        off[m] = fp.src[m * NTHREADS + tid];             // this thread's own entries: no barrier needed
         const int p = min(tid + m * NTHREADS, PBLK - 1);
         const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
-        from[m] = tidx(kk, jj, ii);                      // where this thread's output elements sit in the tile
+        const int rx = ii < PAD ? 0 : (ii < PAD + NPT ? 1 : 2);
+        const int ry = jj < PAD ? 0 : (jj < PAD + NPT ? 1 : 2);
+        const int rz = kk < PAD ? 0 : (kk < PAD + NPT ? 1 : 2);
+        const int lx = ii - PAD + (1 - rx) * NPT, ly = jj - PAD + (1 - ry) * NPT, lz = kk - PAD + (1 - rz) * NPT;
+        off[m] = ghost_source(&gt[(rz * 9 + ry * 3 + rx) * 5], rx, ry, rz, lx, ly, lz);   // the centre entry is the block itself
     }
-    __syncthreads();                                 // the box plan is complete; the plan has left the staging area
 #pragma unroll 1
     for (int v = v0; v < nvar; v += stride) {
         const double* base = zipped + (int64_t)v * nb * BLK;
+        const double* vbase = virt + (int64_t)v * tr.n_virt * BLK;
         double pv[PLAN_FULL];
 #pragma unroll
-        for (int m = 0; m < PLAN_FULL; ++m) pv[m] = ldg(base, off[m]);
-        store_tile<PLAN_FULL, PLAN_FULL>(tile, fp, pv, tid);
-        if (bi.cs[0] >= 0) interp_boxes(tile, scratch, bi, base, tid);   // uniform
-        __syncthreads();
+        for (int m = 0; m < PLAN_FULL; ++m) pv[m] = ldg((off[m] & 1u) ? vbase : base, off[m] & ~1u);
         double* out = padded + ((int64_t)v * nb + b) * PBLK;
 #pragma unroll
         for (int m = 0; m < PLAN_FULL; ++m) {
             const int p = tid + m * NTHREADS;
-            if (p < PBLK) out[p] = tile[from[m]];
+            if (p < PBLK) out[p] = pv[m];
         }
-        __syncthreads();                             // the tile and the staging area are free again
-    }
-}
-
-// Level-ordered ghost fill, centred variant: launched once per level, coarsest first; `blocks` lists
-// the blocks of that level.  Copies and injections as in k_unzip; boxes that come from a coarser
-// leaf are interpolated from that leaf's padded block, which an earlier launch has written.
-__global__ __launch_bounds__(NTHREADS) void k_unzip_centred(DeviceTree tr, const int32_t* __restrict__ blocks, int nvar,
-                                                            const double* __restrict__ zipped, double* padded)
-{
-    __shared__ double tile[TILE];
-    __shared__ double scratch[CENTRED_STAGING];
-    __shared__ BlockInfo bi;
-    static_assert(PLAN_FULL * NTHREADS * sizeof(uint32_t) <= CENTRED_STAGING * sizeof(double), "the plan is built in the staging area");
-    const int tid = threadIdx.x;
-    // workgroup r + G q: variables r, r + G, ... of the q-th block of the list, G = min(8, nvar), as in k_unzip
-    const int stride = nvar < NXCD ? nvar : NXCD;
-    const int64_t q = blockIdx.x / stride, b = blocks[q], nb = tr.nb;
-    const int v0 = (int)(blockIdx.x - q * stride);
-    load_block_info(bi, tr, b, tid);
-    __syncthreads();
-    if (tid == 0) make_box_plan(bi, true);
-    FillPlan<PLAN_FULL> fp;
-    fp.src = reinterpret_cast<uint32_t*>(scratch);   // the staging area is free until the first interpolation
-    make_plan_zipped<PLAN_FULL, PBLK>(fp, bi, tid);
-    uint32_t off[PLAN_FULL];
-    int from[PLAN_FULL];
-#pragma unroll
-    for (int m = 0; m < PLAN_FULL; ++m) {
-        off[m] = fp.src[m * NTHREADS + tid];
-        const int p = min(tid + m * NTHREADS, PBLK - 1);
-        const int ii = p % NP, jj = (p / NP) % NP, kk = p / (NP * NP);
-        from[m] = tidx(kk, jj, ii);
-    }
-    __syncthreads();                                 // the box plan is complete; the plan has left the staging area
-#pragma unroll 1
-    for (int v = v0; v < nvar; v += stride) {
-        const double* base = zipped + (int64_t)v * nb * BLK;
-        double pv[PLAN_FULL];
-#pragma unroll
-        for (int m = 0; m < PLAN_FULL; ++m) pv[m] = ldg(base, off[m]);
-        store_tile<PLAN_FULL, PLAN_FULL>(tile, fp, pv, tid);
-        interp_boxes_centred(tile, scratch, bi, padded + (int64_t)v * nb * PBLK, tid);
-        __syncthreads();
-        double* out = padded + ((int64_t)v * nb + b) * PBLK;
-#pragma unroll
-        for (int m = 0; m < PLAN_FULL; ++m) {
-            const int p = tid + m * NTHREADS;
-            if (p < PBLK) out[p] = tile[from[m]];
-        }
-        __syncthreads();                             // the tile and the staging area are free again
     }
 }
 
@@ -572,26 +518,12 @@ hipError_t launch_kind(const DeviceTree& t, bool zin, Epilogue ep, const RhsArgs
 
 }  // namespace
 
-hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, double* padded, hipStream_t s)
+hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, const double* virt, double* padded, hipStream_t s)
 {
     if (t.nb <= 0 || nvar <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_unzip, dim3((unsigned)(t.nb * (nvar < NXCD ? nvar : NXCD))), dim3(NTHREADS), 0, s, t, nvar, zipped, padded);
+    if (!virt && t.n_virt > 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_unzip, dim3((unsigned)(t.nb * (nvar < NXCD ? nvar : NXCD))), dim3(NTHREADS), 0, s, t, nvar, zipped, virt, padded);
     return hipGetLastError();
-}
-
-hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, int nvar, const double* zipped, double* padded,
-                                hipStream_t s)
-{
-    if (t.nb <= 0 || nvar <= 0) return hipSuccess;
-    for (int l = 0; l < 20; ++l) {                   // coarsest level first; the stream orders the launches
-        const int64_t n = level_start[l + 1] - level_start[l];
-        if (n <= 0) continue;
-        hipLaunchKernelGGL(k_unzip_centred, dim3((unsigned)(n * (nvar < NXCD ? nvar : NXCD))), dim3(NTHREADS), 0, s, t,
-                           t.by_level + level_start[l], nvar, zipped, padded);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
 }
 
 hipError_t launch_virtual(const DeviceTree& t, int nvar, const double* zipped, double* virt, hipStream_t s)

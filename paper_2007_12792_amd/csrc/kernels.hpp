@@ -10,9 +10,6 @@ namespace octfd {
 
 struct DeviceTree {
     const ot_leaf* leaves;   // [nb]
-    const int32_t* ghost;    // [nb][27][5]
-    const int32_t* coarse;   // [nb][32] coarser sources with their boxes (see HostTree); used by the kernels that write padded blocks
-    const int32_t* by_level; // [nb] block ids sorted by level
     int64_t nb;
     // virtual blocks (see HostTree): the ghost table that names them, what each is, and their order by level
     const int32_t* ghost_v;  // [nb][27][5]
@@ -53,10 +50,9 @@ struct RhsArgs {
     double sigma;       // Kreiss-Oliger strength
 };
 
-hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, double* padded, hipStream_t s);
-// level-ordered ghost fill with centred coarse-lattice stencils, padded [nvar][nb][2744]; level_start[21] as in HostTree
-hipError_t launch_unzip_centred(const DeviceTree& t, const int64_t* level_start, int nvar, const double* zipped, double* padded,
-                                hipStream_t s);
+// padded [nvar][nb][2744] from zipped and its virtual blocks (filled by one of the two calls below: which one decides
+// the ghost rule)
+hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, const double* virt, double* padded, hipStream_t s);
 // fills the virtual blocks of a zipped array: virt [nvar][n_virt][512], each the child octant of its source leaf,
 // every point interpolated inside that leaf exactly as a ghost point is in unzip ...
 hipError_t launch_virtual(const DeviceTree& t, int nvar, const double* zipped, double* virt, hipStream_t s);

@@ -161,132 +161,36 @@ int make_ghost_table(const Octree& t, const std::vector<ot_leaf>& leaves, std::v
 
 }  // namespace
 
-// A coarser leaf is a cube and the padded block a box, so the padded points one coarser leaf
-// supplies form a box: the product of per-axis ranges of the three parts {ghost-low, interior,
-// ghost-high}.  A block in the corner of its parent touches at most seven coarser leaves.
-void make_coarse_sources(HostTree& t)
-{
-    const size_t nb = t.leaves.size();
-    t.coarse.assign(nb * kCoarseRow, -1);
-    for (size_t b = 0; b < nb; ++b) {
-        int32_t* out = &t.coarse[b * kCoarseRow];
-        // coarser face neighbours, compacted: count, then (face, leaf id) pairs; face = 2*axis + side
-        int nf = 0;
-        for (int face = 0; face < 6; ++face) {
-            const int ax = face >> 1, step = ax == 0 ? 1 : (ax == 1 ? 3 : 9);
-            const int dir = 13 + ((face & 1) ? step : -step);
-            const int32_t* e = &t.ghost[(b * kDirs + dir) * kEntry];
-            if (e[0] != kCoarser) continue;
-            out[17 + 2 * nf] = face;
-            out[18 + 2 * nf] = e[1];
-            ++nf;
-        }
-        out[16] = nf;
-        int n = 0;
-        int32_t ids[8];
-        int lo[8][3], hi[8][3];
-        for (int dir = 0; dir < kDirs; ++dir) {
-            const int32_t* e = &t.ghost[(b * kDirs + dir) * kEntry];
-            if (e[0] != kCoarser) continue;
-            const int r[3] = {dir % 3, (dir / 3) % 3, dir / 9};
-            int s = 0;
-            while (s < n && ids[s] != e[1]) ++s;
-            if (s == n) {
-                if (n == 8) continue;  // cannot happen on a balanced tree
-                ids[n] = e[1];
-                for (int ax = 0; ax < 3; ++ax) lo[n][ax] = hi[n][ax] = r[ax];
-                ++n;
-            } else {
-                for (int ax = 0; ax < 3; ++ax) {
-                    if (r[ax] < lo[s][ax]) lo[s][ax] = r[ax];
-                    if (r[ax] > hi[s][ax]) hi[s][ax] = r[ax];
-                }
-            }
-        }
-        // sources whose box is one corner of the padded block (ghost part on every axis) go last: kernels that
-        // do not read the corners use only the sources in front of them
-        int m = 0;
-        for (int pass = 0; pass < 2; ++pass) {
-            for (int s = 0; s < n; ++s) {
-                const bool corner = lo[s][0] == hi[s][0] && lo[s][0] != 1 && lo[s][1] == hi[s][1] && lo[s][1] != 1 &&
-                                    lo[s][2] == hi[s][2] && lo[s][2] != 1;
-                if (corner != (pass == 1)) continue;
-                out[2 * m] = ids[s];
-                out[2 * m + 1] = lo[s][0] | (hi[s][0] << 2) | (lo[s][1] << 4) | (hi[s][1] << 6) | (lo[s][2] << 8) | (hi[s][2] << 10);
-                ++m;
-            }
-            if (pass == 0) out[29] = m;
-        }
-    }
-}
-
-void make_level_lists(HostTree& t)
-{
-    const size_t nb = t.leaves.size();
-    int64_t count[21] = {};
-    for (size_t b = 0; b < nb; ++b) ++count[t.leaves[b].level + 1];
-    for (int l = 1; l <= 20; ++l) count[l] += count[l - 1];       // count[l] = first slot of level l
-    for (int l = 0; l <= 20; ++l) t.level_start[l] = count[l];
-    t.by_level.assign(nb, 0);
-    for (size_t b = 0; b < nb; ++b) t.by_level[count[t.leaves[b].level]++] = static_cast<int32_t>(b);
-
-    // the source leaves, found through the coarse-source lists of all blocks
-    t.src_slot.assign(nb, -1);
-    for (size_t b = 0; b < nb; ++b)
-        for (int s = 0; s < 8; ++s) {
-            const int32_t id = t.coarse[b * kCoarseRow + 2 * s];
-            if (id < 0) break;
-            t.src_slot[id] = 0;
-        }
-    int32_t n_src = 0;
-    int64_t scount[21] = {};
-    for (size_t b = 0; b < nb; ++b)
-        if (t.src_slot[b] == 0) {
-            t.src_slot[b] = n_src++;
-            ++scount[t.leaves[b].level + 1];
-        }
-    for (int l = 1; l <= 20; ++l) scount[l] += scount[l - 1];
-    for (int l = 0; l <= 20; ++l) t.src_level_start[l] = scount[l];
-    t.src_by_level.assign(n_src, 0);
-    for (size_t b = 0; b < nb; ++b)
-        if (t.src_slot[b] >= 0) t.src_by_level[scount[t.leaves[b].level]++] = static_cast<int32_t>(b);
-}
-
-// needs src_slot (make_level_lists)
 void make_virtual_blocks(HostTree& t)
 {
     const size_t nb = t.leaves.size();
-    const size_t n_src = t.src_by_level.size();
-    t.vsrc.assign(n_src * kVsrcRow, 0);
     // which child octant of its parent the neighbour octant in direction dir is: the low bit of its anchor
     auto octant_of = [&](size_t b, int dir) {
         const ot_leaf& o = t.leaves[b];
         const uint32_t x = o.ix + (dir % 3 - 1), y = o.iy + ((dir / 3) % 3 - 1), z = o.iz + (dir / 9 - 1);   // mod 2^l keeps the low bit
         return static_cast<int>((x & 1) | ((y & 1) << 1) | ((z & 1) << 2));
     };
-    for (size_t b = 0; b < nb; ++b) {
-        const int32_t slot = t.src_slot[b];
-        if (slot >= 0) t.vsrc[slot * kVsrcRow] = static_cast<int32_t>(b);
-    }
+    // per leaf: which of its child octants some block needs
+    std::vector<uint8_t> mask(nb, 0);
     for (size_t b = 0; b < nb; ++b)
         for (int dir = 0; dir < kDirs; ++dir) {
             const int32_t* e = &t.ghost[(b * kDirs + dir) * kEntry];
-            if (e[0] == kCoarser) t.vsrc[t.src_slot[e[1]] * kVsrcRow + 1] |= 1 << octant_of(b, dir);
+            if (e[0] == kCoarser) mask[e[1]] |= static_cast<uint8_t>(1 << octant_of(b, dir));
         }
+    // numbered by source leaf, then octant
+    std::vector<int32_t> first(nb, 0);
+    t.vblk.clear();
     int32_t n = 0;
-    for (size_t s = 0; s < n_src; ++s) {
-        t.vsrc[s * kVsrcRow + 2] = n;
-        n += __builtin_popcount(static_cast<unsigned>(t.vsrc[s * kVsrcRow + 1]));
+    for (size_t s = 0; s < nb; ++s) {
+        first[s] = n;
+        for (int c = 0; c < 8; ++c)
+            if ((mask[s] >> c) & 1) {
+                t.vblk.push_back(static_cast<int32_t>(s));
+                t.vblk.push_back(c);
+                ++n;
+            }
     }
     t.n_virt = n;
-    t.vblk.clear();
-    t.vblk.reserve(2 * static_cast<size_t>(n));
-    for (size_t s = 0; s < n_src; ++s)
-        for (int c = 0; c < 8; ++c)
-            if ((t.vsrc[s * kVsrcRow + 1] >> c) & 1) {
-                t.vblk.push_back(t.vsrc[s * kVsrcRow]);
-                t.vblk.push_back(c);
-            }
     // by level
     int64_t count[21] = {};
     for (int32_t q = 0; q < n; ++q) ++count[t.leaves[t.vblk[2 * q]].level + 2];      // its own level + 1
@@ -299,10 +203,10 @@ void make_virtual_blocks(HostTree& t)
         for (int dir = 0; dir < kDirs; ++dir) {
             int32_t* e = &t.ghost_v[(b * kDirs + dir) * kEntry];
             if (e[0] != kCoarser) continue;
-            const int32_t* row = &t.vsrc[t.src_slot[e[1]] * kVsrcRow];
             const int c = octant_of(b, dir);
+            const int32_t src = e[1];
             e[0] = kVirtual;
-            e[1] = row[2] + __builtin_popcount(static_cast<unsigned>(row[1]) & ((1u << c) - 1));
+            e[1] = first[src] + __builtin_popcount(static_cast<unsigned>(mask[src]) & ((1u << c) - 1));
         }
 }
 
@@ -356,7 +260,7 @@ int build_tree(const ot_build_params& p, HostTree& out)
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
     const int rc = make_ghost_table(t, out.leaves, out.ghost);
-    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); make_virtual_blocks(out); make_pairs(out); }
+    if (rc == OT_OK) { make_virtual_blocks(out); make_pairs(out); }
     return rc;
 }
 
@@ -383,7 +287,7 @@ int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out)
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
     const int rc = make_ghost_table(t, out.leaves, out.ghost);
-    if (rc == OT_OK) { make_coarse_sources(out); make_level_lists(out); make_virtual_blocks(out); make_pairs(out); }
+    if (rc == OT_OK) { make_virtual_blocks(out); make_pairs(out); }
     return rc;
 }
 

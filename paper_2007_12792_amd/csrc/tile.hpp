@@ -10,7 +10,7 @@ namespace {
 
 constexpr int NPT = 8, PAD = 3, NP = 14, BLK = 512, PBLK = 2744;
 constexpr int NTHREADS = 512;
-constexpr int K_COARSER = 2, K_SAME = 0, K_VIRT = 3;
+constexpr int K_SAME = 0, K_VIRT = 3;   // kinds of a ghost-table entry that are plain copies (1: finer, injection)
 
 // LDS geometry (in doubles).  Rows are stored compactly (stride 14) and planes are padded to a
 // stride of 200 = 8 (mod 32).  A wavefront holds one j row of the block, its lanes run over
@@ -25,28 +25,9 @@ constexpr int TILE = NP * PS;            // 14 planes
 constexpr int WZ = NPT * PS;             // D1_z u on [8 k][14 jj][14 ii]
 constexpr int YPS = NPT * RS + 8;        // plane stride of the D1_y array, 120 = 24 (mod 32)
 constexpr int WY = NPT * YPS;            // D1_y u on [8 k][8 j][14 ii]
-// staging area of the box interpolation in k_unzip: several coarser leaves at once
-constexpr int SCRATCH = WZ + WY + 448;
-
-constexpr int ROUND_SRC = 4;                 // source leaves per round (one register each while in flight)
-struct BoxPlan {
-    int32_t nround;
-    int32_t rbeg[9];                         // round r covers sources rbeg[r] .. rbeg[r+1]-1
-    int32_t n1[8], n2[8], n3[8], bstart[8];  // per round: items of the x / y / z pass, start of region B
-    int32_t o1[8], o2[8], o3[8];             // per source: offset of its items inside its round's pass
-    uint32_t mx[8], mpl[8];                  // per source: magic numbers for dividing by nx and by nx*ny
-    int16_t sx[8], nx[8], sy[8], ny[8], sz[8], nz[8], fx0[8], fy0[8], fz0[8];
-    int16_t face_src[6];                     // for the q-th coarser face: which source (index into the list) it is
-};
-
-struct BlockInfo {       // per-workgroup copy of the block's table rows
-    int32_t gt[27 * 5];
-    int32_t cs[32];      // [0..15] coarse sources: {leaf id, packed region range} x 8, id < 0 ends the
-                         // list, corner-only sources last; [16] number of coarser faces, [17..28] {face, leaf id}
-                         // pairs; [29] number of sources in front of the corner-only ones
-    uint32_t level, ax, ay, az;
-    double lag[36];
-    BoxPlan box;         // filled by make_box_plan()
+struct BlockInfo {       // per-workgroup copy of the block's table row
+    int32_t gt[27 * 5];  // ghost table in which coarser neighbours appear as virtual blocks
+    uint32_t level;
 };
 
 __device__ __forceinline__ int tidx(int kk, int jj, int ii) { return kk * PS + jj * RS + ii; }
@@ -94,17 +75,10 @@ inline unsigned grid_for_blocks(int64_t nb)
     return (unsigned)((nb + span - 1) / span * span);
 }
 
-// VIRT: the ghost table in which coarser neighbours appear as virtual blocks
-template <bool VIRT = false>
 __device__ __forceinline__ void load_block_info(BlockInfo& bi, const DeviceTree& tr, int64_t b, int tid)
 {
-    if (tid < 27 * 5) bi.gt[tid] = (VIRT ? tr.ghost_v : tr.ghost)[b * (27 * 5) + tid];
-    if (tid >= 192 && tid < 192 + 36) bi.lag[tid - 192] = c_lag[tid - 192];
-    if (tid >= 256 && tid < 256 + 32) bi.cs[tid - 256] = tr.coarse[b * 32 + (tid - 256)];
-    if (tid == 320) {
-        const ot_leaf lf = tr.leaves[b];
-        bi.level = lf.level; bi.ax = lf.ix; bi.ay = lf.iy; bi.az = lf.iz;
-    }
+    if (tid < 27 * 5) bi.gt[tid] = tr.ghost_v[b * (27 * 5) + tid];
+    if (tid == 320) bi.level = tr.leaves[b].level;
 }
 
 // ---------------------------------------------------------------- fill plan
@@ -172,7 +146,7 @@ struct FillPlan {
 static_assert(TILE < 65536, "tile indices are packed in pairs");
 
 // Where the point (lx, ly, lz) of the same-level octant in direction (rx, ry, rz) - 1 comes from, given that
-// direction's table entry e (not a coarser one): byte offset into one variable's zipped array (same level: copy;
+// direction's entry e of the table in which coarser neighbours appear as virtual blocks: byte offset into one variable's zipped array (same level: copy;
 // finer: the coinciding node of the child that holds it) or, marked by bit 0, into its array of virtual blocks.
 __device__ __forceinline__ uint32_t ghost_source(const int32_t* e, int rx, int ry, int rz, int lx, int ly, int lz)
 {
@@ -195,10 +169,8 @@ __device__ __forceinline__ uint32_t ghost_source(const int32_t* e, int rx, int r
 }
 
 // Source of every padded point this thread fills, as a byte offset into one variable's zipped
-// array (same-level copy or injection from a finer leaf).  Points whose source is coarser are left
-// to the interpolation passes; with the ghost table that names virtual blocks there are none, and a
-// point inside a virtual block is a same-level copy out of the array of virtual blocks: byte offset
-// into one variable's part of that array, marked by bit 0 (offsets are multiples of 8).
+// array (same-level copy or injection from a finer leaf) or, for a point inside a virtual block, into
+// one variable's part of the array of virtual blocks, marked by bit 0 (offsets are multiples of 8).
 // NPOINTS = how long a prefix of the enumeration is planned.
 template <int NPLAN, int NPOINTS, bool REG>
 __device__ __forceinline__ void make_plan_zipped(FillPlan<NPLAN, REG>& fp, const BlockInfo& bi, int tid)
@@ -214,13 +186,10 @@ __device__ __forceinline__ void make_plan_zipped(FillPlan<NPLAN, REG>& fp, const
             const int rx = ii < PAD ? 0 : (ii < PAD + NPT ? 1 : 2);
             const int ry = jj < PAD ? 0 : (jj < PAD + NPT ? 1 : 2);
             const int rz = kk < PAD ? 0 : (kk < PAD + NPT ? 1 : 2);
-            const int32_t* e = &bi.gt[(rz * 9 + ry * 3 + rx) * 5];
-            if (e[0] != K_COARSER) {
-                // coordinates inside the neighbouring octant of the same level, 0..7
-                const int lx = ii - PAD + (1 - rx) * NPT, ly = jj - PAD + (1 - ry) * NPT, lz = kk - PAD + (1 - rz) * NPT;
-                dst = tidx(kk, jj, ii);
-                src = ghost_source(e, rx, ry, rz, lx, ly, lz);
-            }
+            // coordinates inside the neighbouring octant of the same level, 0..7
+            const int lx = ii - PAD + (1 - rx) * NPT, ly = jj - PAD + (1 - ry) * NPT, lz = kk - PAD + (1 - rz) * NPT;
+            dst = tidx(kk, jj, ii);
+            src = ghost_source(&bi.gt[(rz * 9 + ry * 3 + rx) * 5], rx, ry, rz, lx, ly, lz);
         }
         fp.set_src(m, tid, src);
         fp.set_dst(m, dst);

@@ -1,6 +1,5 @@
-// Host-only check of the derived tables of the library's tree (no GPU, no HIP call): the per-block list of
-// coarser sources (corner-only sources last, their count recorded), the virtual blocks with the ghost table that
-// names them, and the sibling pairs.  Built with g++ together with csrc/octree_host.cpp by tests/test_library_host.py.
+// Host-only check of the derived tables of the library's tree (no GPU, no HIP call): the virtual blocks with the
+// ghost table that names them, and the sibling pairs.  Built with g++ together with csrc/octree_host.cpp by tests/test_library_host.py.
 #include <cmath>
 #include <cstdio>
 #include <vector>
@@ -15,38 +14,6 @@ static int fail(const char* what, long b) { std::printf("FAILED: %s (block %ld)\
 static int check(const HostTree& t)
 {
     const long nb = static_cast<long>(t.leaves.size());
-    long n_coarse_kind = 0;
-    for (long b = 0; b < nb; ++b) {
-        const int32_t* row = &t.coarse[b * kCoarseRow];
-        // sources named by the ghost table, each exactly once
-        int n = 0;
-        while (n < 8 && row[2 * n] >= 0) ++n;
-        int seen_in_table = 0;
-        for (int dir = 0; dir < kDirs; ++dir) {
-            const int32_t* e = &t.ghost[(b * kDirs + dir) * kEntry];
-            if (e[0] != kCoarser) continue;
-            int hit = 0;
-            for (int s = 0; s < n; ++s) hit += row[2 * s] == e[1];
-            if (hit != 1) return fail("a coarser source of the ghost table is not listed exactly once", b);
-            ++seen_in_table;
-        }
-        if ((n > 0) != (seen_in_table > 0)) return fail("source list and ghost table disagree", b);
-        // corner-only sources (ghost part on every axis) come last, and [29] counts the others
-        int first_corner = n;
-        for (int s = 0; s < n; ++s) {
-            const int pk = row[2 * s + 1];
-            bool corner = true;
-            for (int ax = 0; ax < 3; ++ax) {
-                const int lo = (pk >> (4 * ax)) & 3, hi = (pk >> (4 * ax + 2)) & 3;
-                if (lo > hi) return fail("empty range", b);
-                corner = corner && lo == hi && lo != 1;
-            }
-            if (corner && first_corner == n) first_corner = s;
-            if (!corner && first_corner != n) return fail("a corner-only source precedes another source", b);
-        }
-        if (row[29] != first_corner) return fail("count of the sources that are not corner-only", b);
-        n_coarse_kind += row[29] > 0;
-    }
     // virtual blocks: every coarser entry of the ghost table has become a virtual block that is the right child
     // octant of the right source leaf; every virtual block is used, listed once per level, one level below its source
     const long nv = static_cast<long>(t.n_virt);
@@ -110,8 +77,7 @@ static int check(const HostTree& t)
     }
     for (long b = 0; b < nb; ++b)
         if (times[b] != 1) return fail("a block is not covered exactly once by pairs and singles", b);
-    std::printf("blocks %ld, with a coarser source beyond a corner %ld, virtual blocks %ld, pairs %zu, singles %zu\n", nb, n_coarse_kind, nv,
-                t.pairs.size(), t.singles.size());
+    std::printf("blocks %ld, virtual blocks %ld, pairs %zu, singles %zu\n", nb, nv, t.pairs.size(), t.singles.size());
     return 0;
 }
 

@@ -43,9 +43,8 @@ struct RhsLds {
 // Zipped input (ZIN): the tile is filled through the ghost table in which coarser neighbours appear as virtual
 // blocks, which k_virtual or k_virtual_centred has filled before the launch, so every tile entry is a copy or an
 // injection and no interpolation happens here; the two ghost rules differ only in which of the two kernels ran.
-// LIST: the workgroup takes its block from the list of blocks that are not part of a sibling pair (24-field system,
-// whose pairs run k_rhs_pair); otherwise block = position of the workgroup.
-template <int KIND, bool ZIN, int EPI, bool LIST = false>
+// (The 24-field system on zipped input runs k_rhs_pair instead.)
+template <int KIND, bool ZIN, int EPI>
 __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTree tr, RhsArgs a)
 {
     using L = RhsLds<KIND>;
@@ -56,9 +55,8 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
     constexpr int NPLAN = L::NPLAN, NPOINTS = L::NPOINTS;
     constexpr bool PLAN_IN_REGS = L::PLAN_IN_REGS;
 
-    const int64_t q = block_of_workgroup(blockIdx.x);
-    if (q >= (LIST ? tr.n_singles : tr.nb)) return;  // uniform over the workgroup, like everything below
-    const int64_t b = LIST ? (int64_t)tr.singles[q] : q;
+    const int64_t b = block_of_workgroup(blockIdx.x);
+    if (b >= tr.nb) return;                          // uniform over the workgroup, like everything below
 
     const int tid = threadIdx.x;
     const int64_t nb = tr.nb;
@@ -482,15 +480,11 @@ template <int KIND, bool ZIN, int EPI>
 hipError_t launch_one(const DeviceTree& t, const RhsArgs& a, hipStream_t s)
 {
     if constexpr (KIND == OT_RHS_SYN24 && ZIN) {
-        // sibling pairs in the two-block kernel, the few remaining blocks one per workgroup
-        const hipError_t e = launch_rhs_pairs(t, static_cast<Epilogue>(EPI), a, t.pairs, t.n_pairs, s);
-        if (e != hipSuccess) return e;
-        if (t.n_singles > 0)
-            hipLaunchKernelGGL((k_rhs<KIND, true, EPI, true>), dim3(grid_for_blocks(t.n_singles)), dim3(NTHREADS), 0, s, t, a);
+        return launch_rhs_pairs(t, static_cast<Epilogue>(EPI), a, s);
     } else {
-        hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI, false>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
+        hipLaunchKernelGGL((k_rhs<KIND, ZIN, EPI>), dim3(grid_for_blocks(t.nb)), dim3(NTHREADS), 0, s, t, a);
+        return hipGetLastError();
     }
-    return hipGetLastError();
 }
 
 template <int KIND>

@@ -16,13 +16,12 @@ struct DeviceTree {
     const int32_t* vblk;     // [n_virt][2] {source leaf, child octant} of every virtual block
     const int32_t* vlist;    // [n_virt] virtual blocks sorted by level
     int64_t n_virt;
-    // the 24-field system on zipped input: sibling pairs (first block of each) for the two-block kernel, and the
-    // remaining blocks, which run the one-block kernel
-    const int32_t* pairs;
-    int64_t n_pairs;
-    const int32_t* singles;
-    int64_t n_singles;
+    // the 24-field system on zipped input: the work units of the two-block kernel (see HostTree::units)
+    const int32_t* units;
+    int64_t n_units;
 };
+
+constexpr int32_t kUnitSingle = 1 << 30;   // flag on a unit: one block without a partner
 
 // workgroup i runs on XCD i mod kXcds; the kernels deal chunks of kChunk consecutive blocks to the XCDs in turn
 constexpr int kSchedChunk = 16;
@@ -60,9 +59,9 @@ hipError_t launch_virtual(const DeviceTree& t, int nvar, const double* zipped, d
 hipError_t launch_virtual_centred(const DeviceTree& t, const int64_t* vlevel_start, int nvar, const double* zipped, double* virt,
                                    hipStream_t s);
 hipError_t launch_zip(const DeviceTree& t, int nvar, const double* padded, double* zipped, hipStream_t s);
-// the 24-field right-hand side on the sibling pairs of the tree (pair.hip): zipped input with its virtual blocks,
+// the 24-field right-hand side over the units of the tree (pair.hip): zipped input with its virtual blocks,
 // epilogue kOutZipped or one of the Runge-Kutta stages
-hipError_t launch_rhs_pairs(const DeviceTree& t, Epilogue ep, const RhsArgs& args, const int32_t* pairs, int64_t npairs, hipStream_t s);
+hipError_t launch_rhs_pairs(const DeviceTree& t, Epilogue ep, const RhsArgs& args, hipStream_t s);
 // in_zipped = false: args.in is padded; true: args.in is zipped and args.virt holds its virtual blocks
 hipError_t launch_rhs(const DeviceTree& t, ot_rhs_kind kind, bool in_zipped, Epilogue ep, const RhsArgs& args, hipStream_t s);
 

@@ -210,22 +210,21 @@ void make_virtual_blocks(HostTree& t)
         }
 }
 
-void make_pairs(HostTree& t)
+void make_units(HostTree& t)
 {
     const size_t nb = t.leaves.size();
-    t.pairs.clear();
-    t.singles.clear();
+    t.units.clear();
     for (size_t b = 0; b < nb;) {
         const ot_leaf& o = t.leaves[b];
         if (b + 1 < nb && !(o.ix & 1)) {
             const ot_leaf& n = t.leaves[b + 1];
             if (n.level == o.level && n.ix == o.ix + 1 && n.iy == o.iy && n.iz == o.iz) {
-                t.pairs.push_back(static_cast<int32_t>(b));
+                t.units.push_back(static_cast<int32_t>(b));
                 b += 2;
                 continue;
             }
         }
-        t.singles.push_back(static_cast<int32_t>(b));
+        t.units.push_back(static_cast<int32_t>(b) | kUnitSingle);
         ++b;
     }
 }
@@ -260,7 +259,7 @@ int build_tree(const ot_build_params& p, HostTree& out)
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
     const int rc = make_ghost_table(t, out.leaves, out.ghost);
-    if (rc == OT_OK) { make_virtual_blocks(out); make_pairs(out); }
+    if (rc == OT_OK) { make_virtual_blocks(out); make_units(out); }
     return rc;
 }
 
@@ -287,7 +286,7 @@ int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out)
     out.leaves.clear();
     emit_leaves(t, 0, out.leaves);
     const int rc = make_ghost_table(t, out.leaves, out.ghost);
-    if (rc == OT_OK) { make_virtual_blocks(out); make_pairs(out); }
+    if (rc == OT_OK) { make_virtual_blocks(out); make_units(out); }
     return rc;
 }
 

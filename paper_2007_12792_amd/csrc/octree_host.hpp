@@ -30,17 +30,16 @@ struct HostTree {
     std::vector<int32_t> vblk, ghost_v, vlist;
     int64_t n_virt = 0;
     int64_t vlevel_start[21] = {};
-    // Sibling pairs for the two-block kernel of the 24-field system: `pairs` lists the first block of every two
-    // leaves that are the lower and upper x child of one parent (they follow each other in Morton order), `singles`
-    // every other block (a leaf whose x sibling is subdivided).  Both in Morton order; together they cover every
-    // block exactly once.
-    std::vector<int32_t> pairs, singles;
+    // Work units of the two-block kernel of the 24-field system, in Morton order: the first block of every two
+    // leaves that are the lower and upper x child of one parent (they follow each other in storage), and, flagged
+    // with kUnitSingle, every other block (a leaf whose x sibling is subdivided).  Every block belongs to exactly one unit.
+    std::vector<int32_t> units;
 };
 
 // Each returns an OT_* status.
 int build_tree(const ot_build_params& p, HostTree& out);
 int tree_from_leaves(const ot_leaf* leaves, size_t n, HostTree& out);
 void make_virtual_blocks(HostTree& t);
-void make_pairs(HostTree& t);
+void make_units(HostTree& t);
 
 }  // namespace octfd

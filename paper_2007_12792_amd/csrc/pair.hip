@@ -1,4 +1,4 @@
-// gfx950 kernel of the 24-field right-hand side for TWO sibling blocks per workgroup.
+// gfx950 kernel of the 24-field right-hand side on zipped input: TWO sibling blocks per workgroup.
 //
 // Two leaves that are x-neighbours inside one parent follow each other in storage.  One workgroup of
 // 1,024 threads (16 wavefronts, one whole compute unit) owns such a pair as a single 16 x 8 x 8 brick with a
@@ -109,8 +109,12 @@ __device__ __forceinline__ int64_t pair_of_workgroup(int64_t wg)
 
 }  // namespace pr
 
+// A block whose x sibling is subdivided has no partner.  It runs here too, as the first half of a brick whose second
+// half is a phantom: the first three columns of that half are the block's own ghost points beyond its upper x
+// face (taken through the block's own table row), the rest is filled with any valid value, and the threads of the
+// second half go through all the motions (they must meet the barriers) but write nothing to memory.
 template <int EPI>
-__global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, const int32_t* __restrict__ pairs, int64_t npairs)
+__global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a)
 {
     __shared__ double tile[pr::TILE];
     __shared__ double wyz[pr::WZ + pr::WY];          // D1_z u and D1_y u during the second-derivative passes
@@ -123,10 +127,13 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, c
     __shared__ uint32_t s_level;
 
     const int64_t q = pr::pair_of_workgroup(blockIdx.x);
-    if (q >= npairs) return;                         // uniform
+    if (q >= tr.n_units) return;                     // uniform
     const int tid = threadIdx.x;
-    const int64_t b0 = pairs[q], nb = tr.nb;
-    if (tid < 2 * 27 * 5) gt[tid] = tr.ghost_v[b0 * (27 * 5) + tid];   // the rows of b0 and b0 + 1 are adjacent
+    const int32_t unit = tr.units[q];
+    const bool single = unit & kUnitSingle;          // uniform
+    const int64_t b0 = unit & ~kUnitSingle, nb = tr.nb;
+    // the rows of b0 and b0 + 1 are adjacent; a single block's row twice
+    if (tid < 2 * 27 * 5) gt[tid] = tr.ghost_v[b0 * (27 * 5) + (single && tid >= 27 * 5 ? tid - 27 * 5 : tid)];
     if (tid == 320) s_level = tr.leaves[b0].level;
     __syncthreads();
 
@@ -136,26 +143,39 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, c
     const int i = t9 & 7, k = (t9 >> 3) & 7, j = t9 >> 6;
     const int xi = i + NPT * half;                   // 0..15 along the brick
     const int c = (k + PAD) * pr::PS + (j + PAD) * pr::RS + (xi + PAD);
-    const uint32_t o8 = ((uint32_t)(b0 + half) * BLK + (k * NPT + j) * NPT + i) * 8u;
+    const bool phantom = single && half;             // uniform over a wavefront
+    // byte offset of the thread's point inside one variable's zipped array (phantom: of the same point of the real block,
+    // so that everything it loads exists)
+    const uint32_t o8 = ((uint32_t)(b0 + (single ? 0 : half)) * BLK + (k * NPT + j) * NPT + i) * 8u;
     const int lvl = __builtin_amdgcn_readfirstlane((int)s_level);
     const double ih = __longlong_as_double((long long)(1026 + lvl) << 52), ih2 = __longlong_as_double((long long)(1029 + 2 * lvl) << 52);
     const double sigma = a.sigma;
 
-    // fill plan of the ghost points, in registers: source offset (bit 0: virtual block) and tile index
+    // fill plan, in registers: source offset (bit 0: virtual block) and tile index of the thread's ghost points, and the
+    // source of its own point
     uint32_t gsrc[pr::USE_EDGE];
     int gdst[pr::USE_EDGE];
+    auto source = [&](int ii, int jj, int kk) -> uint32_t {
+        int h = ii >= PAD + NPT ? 1 : 0;             // which block's table row: its own part of x and the ghosts beyond it
+        int rx = h ? (ii < PAD + 2 * NPT ? 1 : 2) : (ii < PAD ? 0 : 1);
+        const int ry = jj < PAD ? 0 : (jj < PAD + NPT ? 1 : 2);
+        const int rz = kk < PAD ? 0 : (kk < PAD + NPT ? 1 : 2);
+        int lx = ii - PAD - NPT * h + (1 - rx) * NPT;
+        const int ly = jj - PAD + (1 - ry) * NPT, lz = kk - PAD + (1 - rz) * NPT;
+        if (single && h) {
+            if (ii >= 2 * PAD + NPT) return (uint32_t)b0 * (BLK * 8u);   // phantom region: the real block's first value
+            h = 0; rx = 2; lx = ii - PAD - NPT;      // the real block's ghost columns beyond its upper x face
+        }
+        return ghost_source(&gt[h * (27 * 5) + (rz * 9 + ry * 3 + rx) * 5], rx, ry, rz, lx, ly, lz);
+    };
 #pragma unroll
     for (int m = 0; m < pr::USE_EDGE; ++m) {
         int ii, jj, kk;
         pr::ghost_point(tid + m * pr::NT, ii, jj, kk);
-        const int h = ii >= PAD + NPT ? 1 : 0;       // which block's table row: its own part of x and the ghosts beyond it
-        const int rx = h ? (ii < PAD + 2 * NPT ? 1 : 2) : (ii < PAD ? 0 : 1);
-        const int ry = jj < PAD ? 0 : (jj < PAD + NPT ? 1 : 2);
-        const int rz = kk < PAD ? 0 : (kk < PAD + NPT ? 1 : 2);
-        const int lx = ii - PAD - NPT * h + (1 - rx) * NPT, ly = jj - PAD + (1 - ry) * NPT, lz = kk - PAD + (1 - rz) * NPT;
-        gsrc[m] = ghost_source(&gt[h * (27 * 5) + (rz * 9 + ry * 3 + rx) * 5], rx, ry, rz, lx, ly, lz);
+        gsrc[m] = source(ii, jj, kk);
         gdst[m] = kk * pr::PS + jj * pr::RS + ii;
     }
+    const uint32_t own_src = phantom ? source(xi + PAD, j + PAD, k + PAD) : o8;
     // in a pass that reads the faces only, the second entry of the threads past the face prefix is masked
     const bool face_mask1 = tid + pr::NT >= pr::NGF;
 
@@ -169,7 +189,7 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, c
         constexpr int USE = decltype(use)::value;
         const double* base = var_base(v);
         const double* vbase = virt_base(v);
-        f.own = ldg(base, o8);
+        f.own = ldg((own_src & 1u) ? vbase : base, own_src & ~1u);
 #pragma unroll
         for (int m = 0; m < USE; ++m) {
             uint32_t off = gsrc[m];
@@ -230,7 +250,7 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, c
         off = fma(Gyz, mx.dyz, off);
         const double lap = fma(2.0, off, p.diag);
         lapS[f * pr::NT + tid] = lap;
-        emit<EPI>(a, nb, f, b0, o8, 0u, syn24_combine(p, f, lap, 0.5 * u0, unext), eo);
+        if (!phantom) emit<EPI>(a, nb, f, b0, o8, 0u, syn24_combine(p, f, lap, 0.5 * u0, unext), eo);
         commit(nxt, next_use);
         __syncthreads();                             // the tile is complete; D1_y u, D1_z u may be overwritten
     };
@@ -245,7 +265,7 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, c
         const EpiOperands eo = epi_prefetch<EPI>(a, nb, f, o8);
         if (t <= 13) wyz[(t - 11) * pr::NT + tid] = tile[c];     // u_23, u_22, u_21 for the last three passes
         const Syn24Part p = syn24_axes<false, pr::RS, pr::PS>(tile, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
-        emit<EPI>(a, nb, f, b0, o8, 0u, syn24_combine(p, f, lapS[(f % 10) * pr::NT + tid], 0.5 * u0, unext), eo);
+        if (!phantom) emit<EPI>(a, nb, f, b0, o8, 0u, syn24_combine(p, f, lapS[(f % 10) * pr::NT + tid], 0.5 * u0, unext), eo);
         if (more) {
             __syncthreads();                         // everybody is done with the tile
             commit(nxt, UseFace{});
@@ -267,17 +287,17 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a, c
 
 }  // namespace
 
-hipError_t launch_rhs_pairs(const DeviceTree& t, Epilogue ep, const RhsArgs& a, const int32_t* pairs, int64_t npairs, hipStream_t s)
+hipError_t launch_rhs_pairs(const DeviceTree& t, Epilogue ep, const RhsArgs& a, hipStream_t s)
 {
-    if (npairs <= 0) return hipSuccess;
+    if (t.n_units <= 0) return hipSuccess;
     if (!a.virt && t.n_virt > 0) return hipErrorInvalidValue;
     const int64_t span = pr::PAIR_CHUNK * NXCD;
-    const dim3 grid((unsigned)((npairs + span - 1) / span * span)), block(pr::NT);
+    const dim3 grid((unsigned)((t.n_units + span - 1) / span * span)), block(pr::NT);
     switch (ep) {
-    case kOutZipped: hipLaunchKernelGGL(k_rhs_pair<kOutZipped>, grid, block, 0, s, t, a, pairs, npairs); break;
-    case kRkFirst: hipLaunchKernelGGL(k_rhs_pair<kRkFirst>, grid, block, 0, s, t, a, pairs, npairs); break;
-    case kRkMiddle: hipLaunchKernelGGL(k_rhs_pair<kRkMiddle>, grid, block, 0, s, t, a, pairs, npairs); break;
-    case kRkLast: hipLaunchKernelGGL(k_rhs_pair<kRkLast>, grid, block, 0, s, t, a, pairs, npairs); break;
+    case kOutZipped: hipLaunchKernelGGL(k_rhs_pair<kOutZipped>, grid, block, 0, s, t, a); break;
+    case kRkFirst: hipLaunchKernelGGL(k_rhs_pair<kRkFirst>, grid, block, 0, s, t, a); break;
+    case kRkMiddle: hipLaunchKernelGGL(k_rhs_pair<kRkMiddle>, grid, block, 0, s, t, a); break;
+    case kRkLast: hipLaunchKernelGGL(k_rhs_pair<kRkLast>, grid, block, 0, s, t, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -55,29 +55,34 @@ static int check(const HostTree& t)
         if (v > 0 && (t.vblk[2 * v] < t.vblk[2 * v - 2] || (t.vblk[2 * v] == t.vblk[2 * v - 2] && t.vblk[2 * v + 1] <= t.vblk[2 * v - 1])))
             return fail("order of the virtual blocks", v);
     }
-    // sibling pairs and single blocks: every block exactly once; a pair is the lower and upper x child of one parent
+    // work units of the two-block kernel: every block exactly once, in Morton order; a pair is the lower and upper x
+    // child of one parent, a single block has no leaf as x sibling
     std::vector<int> times(nb, 0);
-    for (int32_t b : t.pairs) {
-        if (b < 0 || b + 1 >= nb) return fail("pair id", b);
-        const ot_leaf &lo = t.leaves[b], &hi = t.leaves[b + 1];
-        if ((lo.ix & 1) || hi.level != lo.level || hi.ix != lo.ix + 1 || hi.iy != lo.iy || hi.iz != lo.iz) return fail("not an x-sibling pair", b);
+    long npairs = 0, nsingles = 0, last = -1;
+    for (int32_t u : t.units) {
+        const long b = u & ~kUnitSingle;
+        if (b < 0 || b >= nb || b <= last) return fail("unit id or order", b);
+        last = b;
         ++times[b];
-        ++times[b + 1];
-    }
-    for (int32_t b : t.singles) {
-        if (b < 0 || b >= nb) return fail("single id", b);
-        ++times[b];
-        // its x sibling must be subdivided: neither neighbour in storage order completes a pair with it
         const ot_leaf& o = t.leaves[b];
-        const long sib = (o.ix & 1) ? b - 1 : b + 1;
-        if (sib >= 0 && sib < nb) {
-            const ot_leaf& n = t.leaves[sib];
-            if (n.level == o.level && (n.ix ^ 1) == o.ix && n.iy == o.iy && n.iz == o.iz) return fail("a single block has a leaf as x sibling", b);
+        if (u & kUnitSingle) {
+            ++nsingles;
+            const long sib = (o.ix & 1) ? b - 1 : b + 1;
+            if (sib >= 0 && sib < nb) {
+                const ot_leaf& n = t.leaves[sib];
+                if (n.level == o.level && (n.ix ^ 1) == o.ix && n.iy == o.iy && n.iz == o.iz) return fail("a single block has a leaf as x sibling", b);
+            }
+        } else {
+            ++npairs;
+            if (b + 1 >= nb) return fail("pair id", b);
+            const ot_leaf& hi = t.leaves[b + 1];
+            if ((o.ix & 1) || hi.level != o.level || hi.ix != o.ix + 1 || hi.iy != o.iy || hi.iz != o.iz) return fail("not an x-sibling pair", b);
+            ++times[b + 1];
         }
     }
     for (long b = 0; b < nb; ++b)
-        if (times[b] != 1) return fail("a block is not covered exactly once by pairs and singles", b);
-    std::printf("blocks %ld, virtual blocks %ld, pairs %zu, singles %zu\n", nb, nv, t.pairs.size(), t.singles.size());
+        if (times[b] != 1) return fail("a block is not covered exactly once by the units", b);
+    std::printf("blocks %ld, virtual blocks %ld, pairs %ld, singles %ld\n", nb, nv, npairs, nsingles);
     return 0;
 }
 

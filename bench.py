@@ -239,8 +239,9 @@ def main():
     copy_gbs = 5 * 2 * n_copy * 8 / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del src, dst
 
-    # dominant kernel = the fused right-hand-side/stage kernel, launched 4 times per step and nothing else
-    # runs in the timed region: average launch duration = region / (4 * steps)
+    # dominant kernel = the fused right-hand-side/stage kernel, launched 4 times per step, each time behind the small
+    # kernel that fills the virtual blocks of its input; nothing else runs in the timed region, and the pair is
+    # priced as one launch: average duration = region / (4 * steps)
     launch_ms = total_ms / (launches_per_step * args.steps)
     bytes_per_launch = sum(stage_bytes) / len(stage_bytes) * nb * 512 * V
     achieved = bytes_per_launch / (launch_ms * 1e-3) / 1e9
@@ -263,9 +264,11 @@ def main():
                    "ms_per_step_all": per_step_ms, "ms_per_step_median": float(np.median(per_step_ms)),
                    "ms_per_step_min": float(min(per_step_ms)), "state_restored_before_each_step": restore,
                    "wall_s_timed_region": wall},
-        "roofline": {"bound": "hbm", "kernel": "k_rhs<%s, zipped in, %s%s> (%d per step)"
-                               % (cfg["kind"], "plain output" if single_rhs else "RK-stage epilogue",
-                                  ", over the launch schedule" if cfg["kind"] == "SYN24" else "", launches_per_step),
+        # one launch = one right-hand-side evaluation: the fill of the virtual blocks (k_virtual, 6 % of the time on
+        # the headline workload) and the fused kernel that does everything else; launch_ms covers both
+        "roofline": {"bound": "hbm", "kernel": "k_virtual + %s<%s, zipped in, %s> (%d per step)"
+                               % ("k_rhs_pair" if cfg["kind"] == "SYN24" else "k_rhs", cfg["kind"],
+                                  "plain output" if single_rhs else "RK-stage epilogue", launches_per_step),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "launch_ms": launch_ms, "algorithmic_bytes_per_launch": bytes_per_launch,
                      # bytes between the L2 caches and the memory fabric per launch (HBM plus whatever the memory-side

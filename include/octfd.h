@@ -117,7 +117,9 @@ int ot_rhs_nvar_out(ot_rhs_kind kind);
  * injection (fine index 2P - 8a') from a finer leaf, or, from a coarser leaf, per axis with
  * f = P - 16a' in [0,16): node f/2 if f is even, else 6-point Lagrange interpolation on that
  * leaf's own nodes s..s+5, s = clamp((f-1)/2 - 2, 0, 2).  Axes are interpolated in the order
- * x, y, z, each as acc = w0*v0, acc = fma(w_m, v_m, acc). */
+ * x, y, z, each as acc = w0*v0, acc = fma(w_m, v_m, acc).
+ * (Like rhs_eval_zipped, the call keeps the virtual blocks of its input in an array owned by the
+ * tree, allocated by the first call that needs it; see there.) */
 int unzip(const ot_tree *tree, int nvar, const double *zipped_dev, double *padded_dev, void *hip_stream);
 
 /* rhs_eval: padded_dev [nvar_in][nb][14^3] -> rhs_padded_dev [nvar_out][nb][14^3]; only the 8^3
@@ -139,7 +141,9 @@ int unzip(const ot_tree *tree, int nvar, const double *zipped_dev, double *padde
  * Operator sequences (h = 2^-(l+3), d_k = u[+k]-u[-k], s_k = u[+k]+u[-k]):
  *   D1 = (fma(45,d1, fma(-9,d2, d3)) * (1/60)) / h;
  *   D2 = (fma(-490,u0, fma(270,s1, fma(-27,s2, 2*s3))) * (1/180)) / h^2;  Laplacian = (D2x+D2y)+D2z;
- *   KO = sigma * (((q_x+q_y)+q_z) / (64 h)),  q = fma(-20,u0, fma(15,s1, fma(-6,s2, s3))). */
+ *   KO = sigma * (((q_x+q_y)+q_z) / (64 h)),  q = fma(-20,u0, fma(15,s1, fma(-6,s2, s3))).
+ * For SYN24 the call uses variables 10..19 of the output array as scratch while it runs (each is
+ * overwritten with its final value before the call's work completes). */
 int rhs_eval(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
              const double *padded_dev, double *rhs_padded_dev, void *hip_stream);
 
@@ -148,9 +152,7 @@ int rhs_eval(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,
 int zip(const ot_tree *tree, int nvar, const double *padded_dev, double *zipped_dev, void *hip_stream);
 
 /* The three calls above fused: zipped in, zipped right-hand side out, no padded array in memory.
- * Bit-identical to zip(rhs_eval(unzip(.))).  For SYN24 both rhs_eval and rhs_eval_zipped use
- * variables 10..19 of the output array as scratch while they run (each is overwritten with its
- * final value before the call's work completes).
+ * Bit-identical to zip(rhs_eval(unzip(.))).
  * How level jumps are handled: where the same-level neighbour octant of a block does not exist
  * because its parent L is a leaf, unzip's rule makes the ghost values there a function of L's data
  * and of the fine position inside L alone.  Such an octant ("virtual block") is therefore filled

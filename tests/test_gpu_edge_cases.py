@@ -269,3 +269,32 @@ def test_random_trees_24_field_right_hand_side(orc, dev, seed):
     got = out.cpu().numpy()
     print("seed %d: %d blocks, levels 3..%d, %d values differ" % (seed, to.n, lmax, int((got != want).sum())), flush=True)
     assert_close(got, want, "random tree %d" % seed)
+
+
+def test_24_field_system_over_many_steps_with_a_stable_time_step(orc, dev):
+    """The prescribed step dt = h/4 is far beyond the explicit stability limit of the 24-field system's second-derivative
+    term, so the benchmark workload cannot be evolved.  With dt = h^2/16 it can (h^2/4 still blows up within ten steps): 24
+    steps of rk_step and of rk_step_centred on
+    the three-level tree, each compared with the oracle's step from the same state, and the state stays bounded."""
+    to, tg = trees(orc, "T4")
+    u0 = sd.make_fields("T4", to.leaves).numpy()
+    dt = 2.0 ** -20                                        # h = 2^-8 on level 5
+    for rule in ("clamped", "centred"):
+        ud = torch.from_numpy(u0).to(dev)
+        ws = torch.empty(tg.rk_workspace_bytes(3) // 8, dtype=torch.float64, device=dev)
+        worst = 0.0
+        for s in range(24):
+            if s % 6 == 0:                                 # the oracle's step from the state the device has reached
+                want = (to.rk4_step_centred if rule == "centred" else to.rk4_step)(3, ud.cpu().numpy(), dt, sigma=sd.KO_SIGMA)
+            (tg.rk_step_centred if rule == "centred" else tg.rk_step)(3, ud, dt, ws, sigma=sd.KO_SIGMA)
+            if s % 6 == 0:
+                got = ud.cpu().numpy()
+                err = np.abs(got - want)
+                bound = 1e-12 * np.abs(want) + 1e-13
+                assert (err <= bound).all(), "%s rule, step %d" % (rule, s)
+                worst = max(worst, float((err / bound).max()))
+        got = ud.cpu().numpy()
+        print("%s rule: 24 steps, max |u| %.4f (start %.4f), worst |diff|/bound against the oracle's step %.3g"
+              % (rule, np.abs(got).max(), np.abs(u0).max(), worst), flush=True)
+        assert np.isfinite(got).all() and np.abs(got).max() < 1.5 * np.abs(u0).max()
+        assert np.abs(got - u0).max() > 1e-6               # it has moved

@@ -165,3 +165,41 @@ def test_centred_step_equals_the_clamped_step_without_level_jumps_and_tracks_a_p
         v = t2.rk4_step_centred(1, v, dt, 0.4)
     exact = np.sin(ph - om * 4 * dt)
     assert np.abs(v[0] - exact).max() < 2e-6
+
+
+def test_F_centred_differentiates_a_polynomial_exactly_across_level_jumps(orc):
+    """F_centred itself against a closed form: the centred rule reproduces polynomials of degree <= 5 in every
+    ghost point, and the sixth-order stencils are exact on them, so on a three-level tree the derivatives of such
+    a polynomial come out exact (to rounding, amplified by 1/h^2) at every point, next to level jumps too."""
+    t = orc.Tree.build(3, 5, np.array([[500000, 520000, 540000]], np.uint32), np.array([60000, 40000], np.uint32))
+    from helpers import away_from_wrap
+    x, y, z = coords(t.leaves)
+    f = poly5(x, y, z)
+    got = t.F_centred(0, f[None])                          # DERIVS: (Dx, Dy, Dz, Laplacian)
+    lv = t.leaves.astype(np.int64)
+    ok = away_from_wrap(t.leaves)
+    for c in (1, 2, 3):
+        ok &= (lv[:, c] >= 2 * (1 << (lv[:, 0] - 3))) & (lv[:, c] < (1 << lv[:, 0]) - 2 * (1 << (lv[:, 0] - 3)))
+    # the same derivatives by central differences of the closed form in much higher precision would need its
+    # symbols; instead differentiate the polynomial numerically with a tiny complex step, which is exact to rounding
+    hstep = 1e-30
+    dx = np.imag(poly5(x + 1j * hstep, y, z)) / hstep
+    dy = np.imag(poly5(x, y + 1j * hstep, z)) / hstep
+    dz = np.imag(poly5(x, y, z + 1j * hstep)) / hstep
+    scale = np.abs(f).max()
+    ih = (8.0 * 2.0 ** lv[:, 0])[:, None, None, None]
+    for name, g, want in (("Dx", got[0], dx), ("Dy", got[1], dy), ("Dz", got[2], dz)):
+        err = np.abs(g - want)[ok]
+        assert err.max() < 1e-13 * scale * ih[ok].max(), name
+    # Laplacian: second complex-step differences lose precision; use the exactness of D2 on degree <= 5 through the
+    # clamped rule's F on a uniform tree of the finest level as the independent reference at the same points
+    fine = lv[:, 0] == 5
+    tu = uniform_tree(orc, 5)
+    xu, yu, zu = coords(tu.leaves)
+    lap_u = tu.F(0, poly5(xu, yu, zu)[None])[3]
+    key = {tuple(r[1:]): i for i, r in enumerate(tu.leaves.astype(np.int64))}
+    sel = np.flatnonzero(ok & fine)
+    assert sel.size > 50
+    idx = np.array([key[tuple(lv[b, 1:])] for b in sel])
+    # (blocks of the uniform tree next to the wrap see a discontinuous periodic extension, but those are excluded)
+    assert np.abs(got[3][sel] - lap_u[idx]).max() < 1e-12 * scale * (8.0 * 32) ** 2

@@ -273,7 +273,8 @@ __global__ __launch_bounds__(NTHREADS) void k_unzip(DeviceTree tr, int nvar, con
 // produces its eight fine values (four pass through, four take the clamped six-point stencil; which ones is the
 // same for all lanes, so the weights are constants).  A wavefront owns one variable of the block: its 64 lanes are
 // the 64 lines of a pass, the passes hand over through a staging array of the wavefront's own, in place, and nothing
-// needs a workgroup barrier.  The eight wavefronts of a workgroup take eight variables of one virtual block at a time.
+// needs a workgroup barrier.  The eight wavefronts of a workgroup take eight variables of one virtual block at a time
+// (or, with fewer variables, of several virtual blocks).
 // (The same passes with one thread per point were bound by LDS instructions: 1.3 ms per call on the 102,075-block tree.)
 
 // the eight fine values r of a child half (O = 0 lower, 1 upper) of a line with nodes v: for odd f = 8 O + i the same
@@ -303,10 +304,14 @@ __global__ __launch_bounds__(NTHREADS) void k_virtual(DeviceTree tr, int nvar, c
 {
     __shared__ double staging[8][NPT * VPS];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    // runs of 16 consecutive virtual blocks (the children of a few source leaves) go to one XCD, whose L2 then serves
+    // with fewer than eight variables a workgroup takes several virtual blocks, so that no wavefront idles:
+    // wavefront w -> virtual block `sub` of the workgroup's `per`, variables v0, v0 + nv, ...
+    const int nv = nvar < 8 ? nvar : 8, per = 8 / nv;
+    const int sub = wave / nv, v0 = wave - sub * nv;
+    // runs of 16 consecutive workgroups (the children of a few source leaves) go to one XCD, whose L2 then serves
     // the re-reads of a source leaf by its other children
-    const int64_t q = block_of_workgroup(blockIdx.x), nb = tr.nb;
-    if (q >= tr.n_virt) return;
+    const int64_t q = block_of_workgroup(blockIdx.x) * per + sub, nb = tr.nb;
+    if (sub >= per || q >= tr.n_virt) return;        // uniform over the wavefront; the kernel has no workgroup barrier
     const int64_t leaf = tr.vblk[2 * q];
     const int oct = tr.vblk[2 * q + 1];
     const int ox = oct & 1, oy = (oct >> 1) & 1, oz = oct >> 2;
@@ -316,18 +321,16 @@ __global__ __launch_bounds__(NTHREADS) void k_virtual(DeviceTree tr, int nvar, c
     const double* in = zipped + leaf * BLK + lane * NPT;        // x pass: this lane's line is (cz, cy) = (hi, lo)
     double* out = virt + q * BLK + lane;                        // z pass: this lane's line is (ty, tx) = (hi, lo)
     double nxt[8];
-    if (wave < nvar) {
 #pragma unroll
-        for (int m = 0; m < 8; ++m) nxt[m] = in[wave * in_stride + m];
-    }
+    for (int m = 0; m < 8; ++m) nxt[m] = in[v0 * in_stride + m];
 #pragma unroll 1
-    for (int v = wave; v < nvar; v += 8) {
+    for (int v = v0; v < nvar; v += nv) {
         double c[8], r[8];
 #pragma unroll
         for (int m = 0; m < 8; ++m) c[m] = nxt[m];
-        if (v + 8 < nvar) {
+        if (v + nv < nvar) {
 #pragma unroll
-            for (int m = 0; m < 8; ++m) nxt[m] = in[(v + 8) * in_stride + m];
+            for (int m = 0; m < 8; ++m) nxt[m] = in[(v + nv) * in_stride + m];
         }
         fine_line(ox, c, r);                                    // (cz, cy) -> fine x
 #pragma unroll
@@ -523,7 +526,8 @@ hipError_t launch_unzip(const DeviceTree& t, int nvar, const double* zipped, con
 hipError_t launch_virtual(const DeviceTree& t, int nvar, const double* zipped, double* virt, hipStream_t s)
 {
     if (t.n_virt <= 0 || nvar <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_virtual, dim3(grid_for_blocks(t.n_virt)), dim3(NTHREADS), 0, s, t, nvar, zipped, virt);
+    const int per = 8 / (nvar < 8 ? nvar : 8);       // virtual blocks per workgroup, as in the kernel
+    hipLaunchKernelGGL(k_virtual, dim3(grid_for_blocks((t.n_virt + per - 1) / per)), dim3(NTHREADS), 0, s, t, nvar, zipped, virt);
     return hipGetLastError();
 }
 

@@ -15,7 +15,7 @@ from helpers import KIND, assert_close, dev_empty, trees
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name,nvar", [("C1", 1), ("T2", 1), ("T4", 3), ("T4", 8), ("T2", 13)])
+@pytest.mark.parametrize("name,nvar", [("C1", 1), ("T2", 1), ("T4", 2), ("T4", 3), ("T3", 5), ("T4", 7), ("T4", 8), ("T2", 13)])
 def test_unzip_and_zip(orc, dev, name, nvar):
     to, tg = trees(orc, name)
     rng = np.random.default_rng(21)

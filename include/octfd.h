@@ -156,7 +156,8 @@ int zip(const ot_tree *tree, int nvar, const double *padded_dev, double *zipped_
  * How level jumps are handled: where the same-level neighbour octant of a block does not exist
  * because its parent L is a leaf, unzip's rule makes the ghost values there a function of L's data
  * and of the fine position inside L alone.  Such an octant ("virtual block") is therefore filled
- * once per call, all 8^3 points, x then y then z exactly as unzip interpolates a ghost point, and
+ * once per call (those of its y rows and z planes that some block reads; the rest is never read
+ * and not written), x then y then z exactly as unzip interpolates a ghost point, and
  * the blocks around it copy from it as from a neighbour of their own level.  The virtual blocks of
  * the input take nvar * (number of virtual blocks) * 4 KB in an array owned by the tree. */
 int rhs_eval_zipped(const ot_tree *tree, ot_rhs_kind kind, const ot_rhs_params *params,

@@ -88,10 +88,10 @@ int ensure_device(const ot_tree* t)
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e);
     // one allocation for all tables, each part 256-byte aligned
     const HostTree& h = t->host;
-    constexpr int kParts = 5;
+    constexpr int kParts = 6;
     auto ibytes = [](const std::vector<int32_t>& v) { return v.size() * sizeof(int32_t); };
-    const void* part[kParts] = {h.leaves.data(), h.ghost_v.data(), h.vblk.data(), h.vlist.data(), h.units.data()};
-    const size_t bytes[kParts] = {h.leaves.size() * sizeof(ot_leaf), ibytes(h.ghost_v), ibytes(h.vblk), ibytes(h.vlist), ibytes(h.units)};
+    const void* part[kParts] = {h.leaves.data(), h.ghost_v.data(), h.vblk.data(), h.vlist.data(), h.units.data(), h.vneed.data()};
+    const size_t bytes[kParts] = {h.leaves.size() * sizeof(ot_leaf), ibytes(h.ghost_v), ibytes(h.vblk), ibytes(h.vlist), ibytes(h.units), ibytes(h.vneed)};
     size_t off[kParts + 1] = {0};
     for (int i = 0; i < kParts; ++i) off[i + 1] = off[i] + (bytes[i] + 255) / 256 * 256;
     char* base = nullptr;
@@ -105,7 +105,7 @@ int ensure_device(const ot_tree* t)
     auto ints = [&](int i) { return reinterpret_cast<const int32_t*>(base + off[i]); };
     t->d_base = base;
     t->dev = DeviceTree{reinterpret_cast<const ot_leaf*>(base + off[0]), static_cast<int64_t>(h.leaves.size()),
-                        ints(1), ints(2), ints(3), h.n_virt, ints(4), static_cast<int64_t>(h.units.size())};
+                        ints(1), ints(2), ints(3), h.n_virt, ints(4), static_cast<int64_t>(h.units.size()), ints(5)};
     t->device = dev;
     return resolve_static_workspace(dev);
 }

@@ -330,8 +330,10 @@ __global__ __launch_bounds__(NTHREADS) void k_virtual(DeviceTree tr, int nvar, c
     if (sub >= per || q >= tr.n_virt) return;        // uniform over the wavefront; the kernel has no workgroup barrier
     const int64_t leaf = tr.vblk[2 * q];
     const int oct = tr.vblk[2 * q + 1];
+    const int need = tr.vneed[q];                                // y rows and z planes that any block reads
     const int ox = oct & 1, oy = (oct >> 1) & 1, oz = oct >> 2;
     const int hi = lane >> 3, lo = lane & 7;
+    const bool row_needed = (need >> hi) & 1;
     double* A = staging[wave];
     const int64_t in_stride = nb * BLK, out_stride = tr.n_virt * BLK;
     const double* in = zipped + leaf * BLK + lane * NPT;        // x pass: this lane's line is (cz, cy) = (hi, lo)
@@ -362,8 +364,10 @@ __global__ __launch_bounds__(NTHREADS) void k_virtual(DeviceTree tr, int nvar, c
 #pragma unroll
         for (int m = 0; m < 8; ++m) c[m] = A[m * VPS + lane];              // line (ty, tx) = (hi, lo) over cz
         fine_line(oz, c, r);
+        // only the rows and planes that are read are written (whole x rows: 64-byte pieces)
 #pragma unroll
-        for (int m = 0; m < 8; ++m) out[v * out_stride + m * (NPT * NPT)] = r[m];
+        for (int m = 0; m < 8; ++m)
+            if (row_needed && ((need >> (8 + m)) & 1)) out[v * out_stride + m * (NPT * NPT)] = r[m];
         __builtin_amdgcn_wave_barrier();                         // the next variable's x pass overwrites the array
     }
 }
@@ -405,6 +409,7 @@ __global__ __launch_bounds__(NTHREADS) void k_virtual_centred(DeviceTree tr, con
     const int64_t q = list[w];
     const int64_t leaf = tr.vblk[2 * q];
     const int oct = tr.vblk[2 * q + 1];
+    const int need = tr.vneed[q];                    // y rows and z planes that any block reads
     if (tid < 27 * 5) gt[tid] = tr.ghost_v[leaf * (27 * 5) + tid];
     __syncthreads();
     for (int p = tid; p < CN * CN * CN; p += NTHREADS) {
@@ -481,7 +486,8 @@ __global__ __launch_bounds__(NTHREADS) void k_virtual_centred(DeviceTree tr, con
         for (int m = 0; m < CN; ++m) c[m] = A[m * CPS + hi * CRS + lo];
         fine_line_centred(c, r);
 #pragma unroll
-        for (int m = 0; m < 8; ++m) out[v * out_stride + m * (NPT * NPT)] = r[m];
+        for (int m = 0; m < 8; ++m)
+            if (((need >> hi) & 1) && ((need >> (8 + m)) & 1)) out[v * out_stride + m * (NPT * NPT)] = r[m];
         __builtin_amdgcn_wave_barrier();                         // the next variable's gather overwrites the array
     }
 }

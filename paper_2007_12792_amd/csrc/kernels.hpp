@@ -19,6 +19,7 @@ struct DeviceTree {
     // the 24-field system on zipped input: the work units of the two-block kernel (see HostTree::units)
     const int32_t* units;
     int64_t n_units;
+    const int32_t* vneed;    // [n_virt] y rows (bits 0..7) and z planes (bits 8..15) of a virtual block that are read at all
 };
 
 constexpr int32_t kUnitSingle = 1 << 30;   // flag on a unit: one block without a partner

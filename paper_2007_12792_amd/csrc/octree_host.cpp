@@ -199,6 +199,10 @@ void make_virtual_blocks(HostTree& t)
     t.vlist.assign(n, 0);
     for (int32_t q = 0; q < n; ++q) t.vlist[count[t.leaves[t.vblk[2 * q]].level + 1]++] = q;
     t.ghost_v = t.ghost;
+    t.vneed.assign(n, 0);
+    // a block reads, of its neighbour in direction d, the three layers next to itself along every axis with d != 0
+    // and all eight along the others
+    auto layers = [](int d) { return d > 0 ? 0x07 : (d < 0 ? 0xE0 : 0xFF); };
     for (size_t b = 0; b < nb; ++b)
         for (int dir = 0; dir < kDirs; ++dir) {
             int32_t* e = &t.ghost_v[(b * kDirs + dir) * kEntry];
@@ -207,6 +211,7 @@ void make_virtual_blocks(HostTree& t)
             const int32_t src = e[1];
             e[0] = kVirtual;
             e[1] = first[src] + __builtin_popcount(static_cast<unsigned>(mask[src]) & ((1u << c) - 1));
+            t.vneed[e[1]] |= layers((dir / 3) % 3 - 1) | layers(dir / 9 - 1) << 8;
         }
 }
 

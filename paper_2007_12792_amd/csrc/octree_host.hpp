@@ -18,7 +18,7 @@ struct HostTree {
     // "Virtual blocks".  Where the same-level neighbour octant of a block does not exist because its parent L is
     // a leaf, the ghost values in that direction are interpolated inside L, and what they are depends only on L's
     // data and on the fine position inside L, not on which block asks.  Such an octant can therefore be filled
-    // once, all 8^3 points of it, like a child of L ("virtual block"), after which the blocks around it read it
+    // once, like a child of L ("virtual block"), after which the blocks around it read it
     // exactly like a neighbour of their own level.
     //   vblk    [n_virt][2]        per virtual block {source leaf id, child octant (ox | oy<<1 | oz<<2)}, ordered by
     //                              source leaf (Morton order), then octant
@@ -27,7 +27,10 @@ struct HostTree {
     //   vlist   [n_virt]           virtual blocks sorted by level (the level of a virtual block is its source leaf's
     //                              plus one): level l occupies vlist[vlevel_start[l] .. vlevel_start[l+1]).  With the
     //                              centred ghost rule a level's virtual blocks read those of the level before.
-    std::vector<int32_t> vblk, ghost_v, vlist;
+    //   vneed   [n_virt]           which y rows (bits 0..7) and z planes (bits 8..15) of a virtual block any block reads: the
+    //                              union, per axis, over the blocks that have it as a neighbour.  The fill writes only
+    //                              those (whole x rows of them); the rest of a virtual block is never read.
+    std::vector<int32_t> vblk, ghost_v, vlist, vneed;
     int64_t n_virt = 0;
     int64_t vlevel_start[21] = {};
     // Work units of the two-block kernel of the 24-field system, in Morton order: the first block of every two

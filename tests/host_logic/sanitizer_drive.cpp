@@ -59,7 +59,7 @@ int main(int argc, char** argv)
         std::mt19937 g(it);
         std::shuffle(lv.begin(), lv.end(), g);
         expect(tree_from_leaves(lv.data(), lv.size(), h2) == OT_OK, "tree from shuffled leaves");
-        expect(h2.ghost == h.ghost && h2.ghost_v == h.ghost_v && h2.vlist == h.vlist && h2.vblk == h.vblk && h2.units == h.units, "same tables from the leaf list");
+        expect(h2.ghost == h.ghost && h2.ghost_v == h.ghost_v && h2.vlist == h.vlist && h2.vblk == h.vblk && h2.vneed == h.vneed && h2.units == h.units, "same tables from the leaf list");
         lv.pop_back();
         expect(tree_from_leaves(lv.data(), lv.size(), h3) == OT_E_INCOMPLETE, "missing leaf");
         lv.push_back(lv[0]);

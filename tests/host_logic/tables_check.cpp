@@ -39,6 +39,28 @@ static int check(const HostTree& t)
             if (t.vblk[2 * v[1] + 1] != static_cast<int32_t>((x & 1) | ((y & 1) << 1) | ((z & 1) << 2))) return fail("child octant of a virtual block", b);
             ++used[v[1]];
         }
+    // the rows and planes of a virtual block that the fill writes are exactly those that some ghost point of some
+    // block lies in: walk every ghost point of every padded block
+    if (static_cast<long>(t.vneed.size()) != nv) return fail("size of the table of needed rows", -1);
+    std::vector<int32_t> seen(nv, 0);
+    for (long b = 0; b < nb; ++b)
+        for (int kk = 0; kk < 14; ++kk)
+            for (int jj = 0; jj < 14; ++jj)
+                for (int ii = 0; ii < 14; ++ii) {
+                    const int r[3] = {ii < 3 ? 0 : (ii < 11 ? 1 : 2), jj < 3 ? 0 : (jj < 11 ? 1 : 2), kk < 3 ? 0 : (kk < 11 ? 1 : 2)};
+                    const int32_t* v = &t.ghost_v[(b * kDirs + r[2] * 9 + r[1] * 3 + r[0]) * kEntry];
+                    if (v[0] != kVirtual) continue;
+                    // position inside the neighbour in that direction
+                    const int ly = jj - 3 + (1 - r[1]) * 8, lz = kk - 3 + (1 - r[2]) * 8;
+                    if (ly < 0 || ly > 7 || lz < 0 || lz > 7) return fail("position inside a virtual block", b);
+                    seen[v[1]] |= 1 << ly | 1 << (8 + lz);
+                }
+    long written = 0;
+    for (long v = 0; v < nv; ++v) {
+        if (t.vneed[v] != seen[v]) return fail("rows and planes of a virtual block that are read", v);
+        written += 8 * __builtin_popcount(seen[v] & 0xFF) * __builtin_popcount(seen[v] >> 8);
+    }
+    if (nv) std::printf("points of the virtual blocks that are written: %.1f %%\n", 100.0 * written / (512.0 * nv));
     std::vector<int> listed(nv, 0);
     for (int l = 0; l < 20; ++l) {
         if (t.vlevel_start[l] > t.vlevel_start[l + 1]) return fail("level ranges of the virtual blocks", l);

@@ -117,17 +117,17 @@ __global__ __launch_bounds__(NTHREADS, waves_per_simd(KIND)) void k_rhs(DeviceTr
         __syncthreads();
         store_tile<NPLAN, PLAN_FACE>(tiles, fp, pv, tid);
         __builtin_amdgcn_sched_barrier(0);
-        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8), e1 = epi_prefetch<EPI>(a, nb, 1, o8);
+        const EpiOperands e0 = epi_prefetch<EPI, ZIN>(a, nb, 0, o8), e1 = epi_prefetch<EPI, ZIN>(a, nb, 1, o8);
         __syncthreads();
         const PointOps pp = point_ops<false>(tiles, c, sigma, ih, ih2);
-        emit<EPI>(a, nb, 0, b, o8, p8, pp.u0 + pu.ko, e0);
-        emit<EPI>(a, nb, 1, b, o8, p8, pu.lap + pp.ko, e1);
+        emit<EPI>(a, nb, 0, b, o8, p8, pp.u0 + pu.ko, ZIN ? with_u<EPI>(e0, pu.u0) : e0);
+        emit<EPI>(a, nb, 1, b, o8, p8, pu.lap + pp.ko, ZIN ? with_u<EPI>(e1, pp.u0) : e1);
     } else if (KIND == OT_RHS_BURGERS) {
         stage(0);
-        const EpiOperands e0 = epi_prefetch<EPI>(a, nb, 0, o8);
+        const EpiOperands e0 = epi_prefetch<EPI, ZIN>(a, nb, 0, o8);
         const PointOps p = point_ops<false>(tiles, c, sigma, ih, ih2);
         const double flux = p.u0 * p.dx;
-        emit<EPI>(a, nb, 0, b, o8, p8, p.ko - flux, e0);
+        emit<EPI>(a, nb, 0, b, o8, p8, p.ko - flux, ZIN ? with_u<EPI>(e0, p.u0) : e0);
     } else {
         // SYN24.  The variables are streamed in descending cyclic order (see syn24_stream).  The
         // first ten real passes (variables 9..0) evaluate the second-derivative combinations Lap_s;
@@ -516,6 +516,7 @@ template <int KIND>
 hipError_t launch_kind(const DeviceTree& t, bool zin, Epilogue ep, const RhsArgs& a, hipStream_t s)
 {
     if (zin && !a.virt && t.n_virt > 0) return hipErrorInvalidValue;
+    if (zin && ep == kRkFirst && a.in != a.u) return hipErrorInvalidValue;   // the first stage takes the state from its input tiles
     if (!zin) {
         switch (ep) {
         case kOutPadded: return launch_one<KIND, false, kOutPadded>(t, a, s);

@@ -240,7 +240,7 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a)
         const int f = syn24_stream(t), f1 = syn24_stream(t + 1);
         prefetch(nxt, f1, next_use);
         const double unext = centre((f + 11) % 24);
-        const EpiOperands eo = epi_prefetch<EPI>(a, nb, f, o8);
+        const EpiOperands eo = with_u<EPI>(epi_prefetch<EPI, true>(a, nb, f, o8), tile[c]);
         const Syn24Part p = syn24_axes<true, pr::RS, pr::PS>(tile, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, Gxx, Gyy, Gzz, sigma, ih, ih2);
         pr::mixed_fill(tile, wy, wz, tid, ih);
         __syncthreads();
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(pr::NT) void k_rhs_pair(DeviceTree tr, RhsArgs a)
         const int f = syn24_stream(t);
         const bool more = t + 1 < NSTREAM;
         if (more) prefetch(nxt, syn24_stream(t + 1), UseFace{});
-        const EpiOperands eo = epi_prefetch<EPI>(a, nb, f, o8);
+        const EpiOperands eo = with_u<EPI>(epi_prefetch<EPI, true>(a, nb, f, o8), tile[c]);
         if (t <= 13) wyz[(t - 11) * pr::NT + tid] = tile[c];     // u_23, u_22, u_21 for the last three passes
         const Syn24Part p = syn24_axes<false, pr::RS, pr::PS>(tile, c, wy, wz, owny, ownz, nx, ny, nz, bx, by, bz, 0.0, 0.0, 0.0, sigma, ih, ih2);
         if (!phantom) emit<EPI>(a, nb, f, b0, o8, 0u, syn24_combine(p, f, lapS[(f % 10) * pr::NT + tid], 0.5 * u0, unext), eo);

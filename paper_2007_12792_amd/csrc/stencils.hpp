@@ -122,13 +122,22 @@ __device__ __forceinline__ Mixed mixed_derivs(const double* tile, double* wy, do
 // padded block; w selects the variable and b the block (both uniform).
 struct EpiOperands { double acc, u; };
 
-template <int EPI>
+// U_FROM_TILE: in the first stage the input of the right-hand side is the state itself (the launcher checks it), so
+// the state at the thread's point is the centre of the variable's tile and is not loaded again: the kernel hands it
+// over with with_u() once it has it.
+template <int EPI, bool U_FROM_TILE = false>
 __device__ __forceinline__ EpiOperands epi_prefetch(const RhsArgs& a, int64_t nb, int w, uint32_t o8)
 {
     EpiOperands e{0.0, 0.0};
     const int64_t f = (int64_t)w * nb * BLK;
-    if (EPI == kRkFirst || EPI == kRkMiddle || EPI == kRkLast) e.u = ldg(a.u + f, o8);
+    if ((EPI == kRkFirst && !U_FROM_TILE) || EPI == kRkMiddle || EPI == kRkLast) e.u = ldg(a.u + f, o8);
     if (EPI == kRkMiddle || EPI == kRkLast) e.acc = ldg(a.acc + f, o8);
+    return e;
+}
+template <int EPI>
+__device__ __forceinline__ EpiOperands with_u(EpiOperands e, double centre)
+{
+    if (EPI == kRkFirst) e.u = centre;
     return e;
 }
 
